@@ -1,0 +1,150 @@
+/*
+ * CPU oracle for the block-wise causal attention of Next-Frame Diffusion.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain statement of what the
+ * attention computes; it shares no code, header, table or helper with the HIP
+ * library and is never on the product path.  Only the test-suite, the smoke
+ * check and the benchmark's cpu_baseline leg may build or call it.
+ *
+ * Everything is fp64.  Inputs are the exact values the device kernel receives
+ * (bf16 / fp32 widen to fp64 without rounding).
+ *
+ * The mask follows the paper's "Block-wise Causal Attention" paragraph
+ * (Sec. 3.1): a token attends to every token of its own frame and to every
+ * token of all preceding frames, never to a later frame.  The queries are the
+ * last q_frames of the kv_frames frames present, as in the speculative
+ * sampling listing of Appendix A (a chunk of new frames is appended at the end
+ * and only those frames are produced) and in the KV-cache paragraph of
+ * Appendix B (past frames' K/V are reused, only the new frames are queried).
+ * Softmax is the ordinary one with natural exponent; the paper does not write
+ * it out.
+ *
+ * Pins (tests/test_oracle_pins.py): reduction to textbook causal attention at
+ * T=1 and to full attention at one frame (both against independent numpy and
+ * a library SDPA), brute force over an explicit mask matrix, uniform-score
+ * closed form (mean of visible V), future-perturbation invariance, cached /
+ * speculative forms equal to the tail rows of the full form, visible-pair
+ * count closed form, permutation and convexity invariants, one-hot limit and
+ * large-magnitude stability.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+/* Frame-block visibility (Sec. 3.1, "Block-wise Causal Attention").
+ * Query row i lives in query-frame i/T, which is absolute frame P + i/T where
+ * P = kv_frames - q_frames past frames precede the first query frame.
+ * Key j lives in absolute frame j/T.  Visible iff key frame <= query frame. */
+static int visible(int64_t i, int64_t j, int64_t T, int64_t P)
+{
+    return (j / T) <= (P + i / T);
+}
+
+/*
+ * out[b,h,r,:] = sum_j w_j v[b,h,j,:] / sum_j w_j,   w_j = M_ij exp(s_ij - m_i)
+ * s_ij = scale * <q[b,h,i,:], k[b,h,j,:]>,  m_i = max over visible j of s_ij,
+ * where i = rows[r] (or r when rows == NULL).
+ *
+ * q   : [B, H, q_frames*T, D]        k, v : [B, H, F*T, D]  (first kv_frames*T rows used)
+ * out : [B, H, n_out, D], n_out = n_rows if rows != NULL else q_frames*T
+ * Returns 0, or -1 on bad arguments / allocation failure.
+ */
+int nfd_oracle_block_causal_attn(const double *q, const double *k, const double *v,
+                                 double *out, int B, int H, int F, int T, int D,
+                                 int kv_frames, int q_frames, double scale,
+                                 const int64_t *rows, int64_t n_rows)
+{
+    if (!q || !k || !v || !out) return -1;
+    if (B < 1 || H < 1 || T < 1 || D < 1 || q_frames < 1) return -1;
+    if (q_frames > kv_frames || kv_frames > F) return -1;
+
+    const int64_t Sq = (int64_t)q_frames * T;
+    const int64_t Sk = (int64_t)kv_frames * T;
+    const int64_t Scap = (int64_t)F * T;
+    const int64_t P = (int64_t)kv_frames - q_frames;
+    const int64_t n_out = rows ? n_rows : Sq;
+    if (rows) {
+        for (int64_t r = 0; r < n_rows; ++r)
+            if (rows[r] < 0 || rows[r] >= Sq) return -1;
+    }
+    int failed = 0;
+
+#pragma omp parallel
+    {
+        double *w = (double *)malloc((size_t)Sk * sizeof(double));
+        unsigned char *M = (unsigned char *)malloc((size_t)Sk);
+        if (!w || !M) {
+#pragma omp atomic write
+            failed = 1;
+        }
+#pragma omp barrier
+        if (!failed) {
+#pragma omp for collapse(2) schedule(dynamic, 8)
+            for (int64_t bh = 0; bh < (int64_t)B * H; ++bh) {
+                for (int64_t r = 0; r < n_out; ++r) {
+                    const int64_t i = rows ? rows[r] : r;
+                    const double *qi = q + (bh * Sq + i) * D;
+                    const double *kb = k + bh * Scap * D;
+                    const double *vb = v + bh * Scap * D;
+                    double *o = out + (bh * n_out + r) * D;
+
+                    /* explicit boolean mask row, then masked scores */
+                    double m = -INFINITY;
+                    for (int64_t j = 0; j < Sk; ++j) {
+                        M[j] = (unsigned char)visible(i, j, T, P);
+                        if (!M[j]) { w[j] = 0.0; continue; }
+                        double s = 0.0;
+                        for (int d = 0; d < D; ++d) s += qi[d] * kb[j * D + d];
+                        s *= scale;
+                        w[j] = s;
+                        if (s > m) m = s;
+                    }
+                    double denom = 0.0;
+                    for (int d = 0; d < D; ++d) o[d] = 0.0;
+                    for (int64_t j = 0; j < Sk; ++j) {
+                        if (!M[j]) continue;
+                        const double e = exp(w[j] - m);
+                        denom += e;
+                        for (int d = 0; d < D; ++d) o[d] += e * vb[j * D + d];
+                    }
+                    for (int d = 0; d < D; ++d) o[d] /= denom;
+                }
+            }
+        }
+        free(w);
+        free(M);
+    }
+    return failed ? -1 : 0;
+}
+
+/*
+ * KV cache write (Appendix B, "KV Caching": K/V of frames are computed once
+ * and reused).  Copies n_frames new frames into the cache at frame frame_pos.
+ * cache : [B, H, F*T, D]   fresh : [B, H, n_frames*T, D]
+ */
+int nfd_oracle_kvcache_append(double *cache, const double *fresh, int B, int H,
+                              int F, int T, int D, int frame_pos, int n_frames)
+{
+    if (!cache || !fresh) return -1;
+    if (B < 1 || H < 1 || T < 1 || D < 1 || n_frames < 0 || frame_pos < 0) return -1;
+    if (frame_pos + n_frames > F) return -1;
+    const int64_t rowsz = (int64_t)T * D;
+    for (int64_t bh = 0; bh < (int64_t)B * H; ++bh)
+        for (int64_t f = 0; f < n_frames; ++f)
+            memcpy(cache + (bh * F + frame_pos + f) * rowsz,
+                   fresh + (bh * n_frames + f) * rowsz, (size_t)rowsz * sizeof(double));
+    return 0;
+}
+
+/* Number of visible (query, key) pairs per (b, h), by direct enumeration of
+ * the mask (used to state FLOP counts; closed form is checked in the tests). */
+int64_t nfd_oracle_visible_pairs(int T, int kv_frames, int q_frames)
+{
+    const int64_t Sq = (int64_t)q_frames * T, Sk = (int64_t)kv_frames * T;
+    const int64_t P = (int64_t)kv_frames - q_frames;
+    int64_t n = 0;
+    for (int64_t i = 0; i < Sq; ++i)
+        for (int64_t j = 0; j < Sk; ++j) n += visible(i, j, T, P);
+    return n;
+}

@@ -1,0 +1,114 @@
+"""ctypes front-end of the fp64 CPU oracle in ``nfd_oracle.c``.
+
+TEST INFRASTRUCTURE ONLY: imported by ``tests/``, by the smoke check and by the
+benchmark's cpu_baseline leg, never by the product package.  It holds no
+arithmetic of its own: it widens the inputs to fp64 (exact for bf16 and fp32
+values), calls the C routine and returns fp64.
+
+The C source is compiled with gcc on first use (``build()``); the shared
+object sits next to the source.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "nfd_oracle.c")
+_LIB = os.path.join(_HERE, "libnfd_oracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (-O2, OpenMP, no fast-math)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + ".tmp%d" % os.getpid()
+        subprocess.check_call(
+            ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c11", "-Wall", "-o", tmp, _SRC, "-lm"]
+        )
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        lib = ctypes.CDLL(build())
+        dp = ctypes.POINTER(ctypes.c_double)
+        ip = ctypes.POINTER(ctypes.c_int64)
+        lib.nfd_oracle_block_causal_attn.argtypes = [dp, dp, dp, dp] + [ctypes.c_int] * 7 + [
+            ctypes.c_double, ip, ctypes.c_int64]
+        lib.nfd_oracle_block_causal_attn.restype = ctypes.c_int
+        lib.nfd_oracle_kvcache_append.argtypes = [dp, dp] + [ctypes.c_int] * 7
+        lib.nfd_oracle_kvcache_append.restype = ctypes.c_int
+        lib.nfd_oracle_visible_pairs.argtypes = [ctypes.c_int] * 3
+        lib.nfd_oracle_visible_pairs.restype = ctypes.c_int64
+        _lib = lib
+    return _lib
+
+
+def _f64(a):
+    return np.ascontiguousarray(np.asarray(a, dtype=np.float64))
+
+
+def _ptr(a):
+    return a.ctypes.data_as(ctypes.POINTER(ctypes.c_double))
+
+
+def block_causal_attn(q, k, v, T, kv_frames=None, q_frames=None, scale=None, rows=None):
+    """Block-wise causal attention (Sec. 3.1), fp64.
+
+    q: [B,H,q_frames*T,D]; k, v: [B,H,F*T,D] with the first kv_frames*T rows valid.
+    rows: optional 1-D int array of query-row indices; then only those rows are
+    computed and the result is [B,H,len(rows),D].
+    """
+    q, k, v = _f64(q), _f64(k), _f64(v)
+    B, H, Sq, D = q.shape
+    if k.shape != v.shape or k.shape[:2] != (B, H) or k.shape[3] != D:
+        raise ValueError("k/v shape mismatch")
+    if Sq % T or k.shape[2] % T:
+        raise ValueError("sequence lengths must be multiples of T")
+    F = k.shape[2] // T
+    if q_frames is None:
+        q_frames = Sq // T
+    if kv_frames is None:
+        kv_frames = F
+    if q_frames * T != Sq:
+        raise ValueError("q rows != q_frames*T")
+    if scale is None:
+        scale = 1.0 / np.sqrt(D)
+    if rows is not None:
+        rows = np.ascontiguousarray(np.asarray(rows, dtype=np.int64))
+        n_rows = rows.shape[0]
+        rp = rows.ctypes.data_as(ctypes.POINTER(ctypes.c_int64))
+        out = np.empty((B, H, n_rows, D), dtype=np.float64)
+    else:
+        n_rows, rp = 0, None
+        out = np.empty((B, H, Sq, D), dtype=np.float64)
+    rc = _load().nfd_oracle_block_causal_attn(
+        _ptr(q), _ptr(k), _ptr(v), _ptr(out), B, H, F, T, D, kv_frames, q_frames,
+        float(scale), rp, n_rows)
+    if rc != 0:
+        raise ValueError("oracle rejected the arguments (rc=%d)" % rc)
+    return out
+
+
+def kvcache_append(cache, fresh, T, frame_pos):
+    """Write the frames of ``fresh`` into ``cache`` at frame ``frame_pos`` (Appendix B).
+    Returns a new fp64 array; the input cache is not modified."""
+    cache, fresh = _f64(cache).copy(), _f64(fresh)
+    B, H, Sc, D = cache.shape
+    n_frames = fresh.shape[2] // T
+    rc = _load().nfd_oracle_kvcache_append(_ptr(cache), _ptr(fresh), B, H, Sc // T, T, D,
+                                           frame_pos, n_frames)
+    if rc != 0:
+        raise ValueError("oracle rejected the arguments (rc=%d)" % rc)
+    return cache
+
+
+def visible_pairs(T, kv_frames, q_frames):
+    """Count of visible (query, key) pairs per head, by enumeration of the mask."""
+    return int(_load().nfd_oracle_visible_pairs(T, kv_frames, q_frames))
