@@ -1,0 +1,143 @@
+#!/usr/bin/env python3
+"""Benchmark of the block-wise causal attention hot path on one MI355X.
+
+One "step" is one pass of the hot path over one batch of synthetic input: for the
+training form the forward call; for the cached forms the cache append of the new
+frames followed by the forward call.  Inputs are resident in HBM before the timed
+region.  Prints ONE JSON line on stdout.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 matrix-core peak (published)
+PEAK_HBM_GBS = 8000.0      # MI355X HBM3E peak (published)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="c2_train")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of the oracle sample")
+    ap.add_argument("--all", action="store_true", help="also time the other workloads (reported on stderr)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2506_01380_amd import binding as nb
+    from paper_2506_01380_amd import workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    torch.cuda.set_device(0)
+    attn = nb.Attention("bf16")
+
+    def time_workload(name, steps, warmup, rotate=1):
+        cfg = wl.CONFIGS[name]
+        B, H, D, T, kvf, qf, F = (cfg[x] for x in ("B", "H", "D", "T", "kv_frames", "q_frames", "F"))
+        gen = torch.Generator(device="cuda").manual_seed(cfg["seed"])
+        mk = lambda *s: torch.randn(*s, device="cuda", generator=gen, dtype=torch.float32).to(torch.bfloat16)
+        cached = qf < kvf
+        sets = []
+        for _ in range(rotate):
+            q, k, v = mk(B, H, qf * T, D), mk(B, H, F * T, D), mk(B, H, F * T, D)
+            kn = k[:, :, (kvf - qf) * T: kvf * T].clone() if cached else None
+            vn = v[:, :, (kvf - qf) * T: kvf * T].clone() if cached else None
+            sets.append((q, k, v, torch.empty_like(q), kn, vn))
+
+        def step(i):
+            q, k, v, out, kn, vn = sets[i % rotate]
+            if cached:
+                nb.nfd_kvcache_append(attn.h, k, v, kn, vn, B, H, F, T, D, kvf - qf, qf)
+            nb.nfd_block_causal_attn_fwd(attn.h, q, k, v, out, B, H, F, T, D, kvf, qf)
+
+        for i in range(warmup):
+            step(i)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(steps):
+            step(i)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / steps
+        flops = nb.unmasked_flops(B, H, D, T, kvf, qf)
+        min_bytes = (2 * kvf * T + 2 * qf * T) * D * 2 * B * H
+        return dict(workload=name, ms_per_step=ms, tflops=flops / ms * 1e-9, gbs=min_bytes / ms * 1e-6,
+                    frames_per_s=B * qf / ms * 1e3, flops=flops, min_bytes=min_bytes, cfg=cfg,
+                    plan=nb.nfd_attn_plan(nb.NFD_BF16, B, H, F, T, D, kvf, qf))
+
+    main_res = time_workload(args.workload, args.steps, args.warmup)
+    cfg = main_res["cfg"]
+
+    others = []
+    if args.all:
+        for name in wl.CONFIGS:
+            if name == args.workload or wl.CONFIGS[name]["dtype"] != "bf16":
+                continue
+            steps = 20 if name == "c5a_long_train" else 200
+            r = time_workload(name, steps, 10, rotate=16 if "decode" in name or "spec" in name else 1)
+            r.pop("cfg")
+            others.append(r)
+            print(json.dumps(r), file=sys.stderr, flush=True)
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import nfd_oracle as orc
+        B, H, D, T, kvf, qf = (cfg[x] for x in ("B", "H", "D", "T", "kv_frames", "q_frames"))
+        _, q, k, v = wl.make_config(args.workload)
+        cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+
+        def run_rows(per_frame):
+            rows = wl.sample_rows(T, qf, per_frame, cfg["seed"])
+            t0 = time.perf_counter()
+            orc.block_causal_attn(q, k, v, T, kv_frames=kvf, q_frames=qf, rows=rows)
+            dt = time.perf_counter() - t0
+            P = kvf - qf
+            pairs = sum((P + r // T + 1) * T for r in rows) * B * H
+            return dt, 4 * D * pairs, len(rows)
+
+        dt, fl, n = run_rows(0)  # two rows per frame: calibration (includes fp64 widening of the inputs)
+        per_frame = int(max(1, min(T - 2, (args.cpu_seconds / max(dt, 1e-3)) * 2 - 2)))
+        dt, fl, n = run_rows(per_frame)
+        cpu = dict(value=fl / dt * 1e-12, unit="TFLOP/s", cores=cores, kind="oracle",
+                   sample="%d of %d query rows per head (first+last+%d random rows of each frame), all %d heads, %.1f s"
+                          % (n, qf * T, per_frame, B * H, dt))
+
+    frac = main_res["tflops"] / PEAK_BF16_TFLOPS
+    line = {
+        "metric": "block-causal attn TFLOP/s (unmasked) + % bf16 MFMA peak; attn-layer frames/s",
+        "value": round(main_res["tflops"], 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(main_res["ms_per_step"], 5), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": args.workload, "B": cfg["B"], "H": cfg["H"], "D": cfg["D"], "T": cfg["T"],
+                   "kv_frames": cfg["kv_frames"], "q_frames": cfg["q_frames"],
+                   "pct_bf16_mfma_peak": round(100 * frac, 2),
+                   "attn_layer_frames_per_s": round(main_res["frames_per_s"], 1), "plan": main_res["plan"]},
+        "roofline": {"bound": "mfma", "achieved": round(main_res["tflops"], 2), "peak": PEAK_BF16_TFLOPS,
+                     "unit": "TFLOP/s", "frac": round(frac, 4), "traffic": None,
+                     "kernel": "attn_fwd_bf16_d64"},
+        "cpu_baseline": cpu,
+    }
+    if others:
+        line["other_workloads"] = [{k: (round(v, 4) if isinstance(v, float) else v) for k, v in r.items()
+                                    if k in ("workload", "ms_per_step", "tflops", "gbs", "frames_per_s")} for r in others]
+    attn.close()
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,137 @@
+/*
+ * nfd_attn.h - C ABI of the MI355X (gfx950) block-wise causal attention library.
+ *
+ * The operation is the attention of Next-Frame Diffusion (Sec. 3.1, paragraph
+ * "Block-wise Causal Attention"): the token sequence is a run of frames of T
+ * tokens each; a token attends to every token of its own frame and to every
+ * token of all preceding frames, and to nothing in later frames.  The three
+ * call forms of the paper map onto one entry point through (kv_frames,
+ * q_frames):
+ *   training / full sequence : q_frames == kv_frames            (Sec. 3.1)
+ *   single-frame inference   : q_frames == 1 over cached frames (Appendix B, "KV Caching")
+ *   speculative inference    : q_frames == N new frames over cached frames, block-causal
+ *                              among themselves (Sec. 4.2; Appendix A listing)
+ * The queries are always the LAST q_frames of the kv_frames frames held in k/v.
+ *
+ * All pointers named q, k, v, out, *_cache, *_new are DEVICE pointers on the
+ * handle's device.  Tensors are dense and row-major.  Nothing here takes or
+ * returns a torch type.  All work is enqueued on the caller's stream and the
+ * calls do not synchronise with the host.  A handle may be used by one host
+ * thread at a time; calls on one handle must be stream-ordered with respect
+ * to each other (they share the handle's workspace).
+ */
+#ifndef NFD_ATTN_H
+#define NFD_ATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct nfd_attn nfd_attn_t; /* opaque; owns only its workspace */
+
+typedef enum { NFD_BF16 = 0, NFD_FP32 = 1 } nfd_dtype_t;
+
+enum {
+    NFD_OK = 0,
+    NFD_ERR_NULL = -1,        /* a required pointer is NULL */
+    NFD_ERR_SHAPE = -2,       /* a dimension < 1, or q_frames > kv_frames, or n_frames < 0 ... */
+    NFD_ERR_UNSUPPORTED = -3, /* dtype / head width not built */
+    NFD_ERR_CAPACITY = -4,    /* kv_frames > F, or frame_pos + n_frames > F */
+    NFD_ERR_HIP = -5,         /* a HIP runtime call failed (text in nfd_last_error) */
+    NFD_ERR_ALLOC = -6        /* host or device allocation failed */
+};
+
+/*
+ * Create a handle for tensors of `dtype` on HIP device `device`.
+ * workspace_bytes: device scratch owned by the handle, used for the partial
+ * results of key-split launches (small query counts over a long cache); 0
+ * selects a default (128 MiB).  A call whose ideal split does not fit the
+ * workspace uses fewer splits; it never fails for that reason.
+ * Allocates; not to be called under stream capture.
+ * Errors: NFD_ERR_NULL (h), NFD_ERR_UNSUPPORTED (dtype), NFD_ERR_HIP, NFD_ERR_ALLOC.
+ */
+int nfd_attn_create(nfd_attn_t** h, nfd_dtype_t dtype, int device, size_t workspace_bytes);
+
+/*
+ * Block-wise causal attention forward (Sec. 3.1; cached and speculative forms:
+ * Appendix B "KV Caching", Sec. 4.2 and the Appendix A listing).
+ *
+ *   P = kv_frames - q_frames                      past frames before the first query frame
+ *   query row i in [0, q_frames*T), key j in [0, kv_frames*T)
+ *   visible(i, j)  <=>  floor(j / T) <= P + floor(i / T)
+ *   out[b,h,i,:] = softmax_j( scale * <q[b,h,i,:], k[b,h,j,:]> over visible j ) . v[b,h,j,:]
+ *
+ * q, out : [B, H, q_frames*T, D]
+ * k, v   : [B, H, F*T, D]; F is the frame CAPACITY (head stride = F*T*D elements);
+ *          only the first kv_frames*T rows of each head are read.  The K/V of the
+ *          query frames themselves must already be in k, v (append first).
+ * dtype of all four tensors is the handle's; bf16 computes on bf16 matrix cores
+ * with fp32 accumulation and rounds the output to nearest-even; fp32 computes in fp32.
+ * scale <= 0 selects 1/sqrt(D).  stream: a hipStream_t (NULL = default stream).
+ * Supported: any B, H, T >= 1; D = 64 for bf16 on the matrix-core path, every other
+ * D <= 256 and all fp32 shapes on the general path.  The device current on the calling
+ * thread must be the handle's device.
+ * Ownership: the caller owns all four tensors; the library keeps no reference.
+ * Errors (checked before any launch, in this order): NFD_ERR_NULL, NFD_ERR_SHAPE,
+ * NFD_ERR_CAPACITY, NFD_ERR_UNSUPPORTED; NFD_ERR_HIP if a launch fails.
+ */
+int nfd_block_causal_attn_fwd(nfd_attn_t* h, const void* q, const void* k, const void* v, void* out,
+                              int B, int H, int F, int T, int D, int kv_frames, int q_frames,
+                              float scale, void* stream);
+
+/*
+ * Write the K and V of n_frames new frames into the cache at frame frame_pos
+ * (Appendix B, "KV Caching": K/V of a frame are computed once and reused by
+ * every later denoising step and frame).
+ * k_cache, v_cache : [B, H, F*T, D]      k_new, v_new : [B, H, n_frames*T, D]
+ * Frames [frame_pos, frame_pos + n_frames) of every head are overwritten; this
+ * is also how a rejected speculation is rolled back (Sec. 4.2): pass a smaller
+ * kv_frames to the next forward and append from the last accepted frame.
+ * n_frames == 0 is a no-op.  Errors: NFD_ERR_NULL, NFD_ERR_SHAPE,
+ * NFD_ERR_CAPACITY (frame_pos + n_frames > F), NFD_ERR_UNSUPPORTED, NFD_ERR_HIP.
+ */
+int nfd_kvcache_append(nfd_attn_t* h, void* k_cache, void* v_cache, const void* k_new,
+                       const void* v_new, int B, int H, int F, int T, int D, int frame_pos,
+                       int n_frames, void* stream);
+
+/* Free the handle and its workspace.  NULL is accepted. */
+int nfd_attn_destroy(nfd_attn_t* h);
+
+/* Text of the last error on this handle ("" if none); valid until the next call on it. */
+const char* nfd_last_error(const nfd_attn_t* h);
+
+/* ---- host-only helpers: no GPU needed, no HIP call made ------------------------------- */
+
+/* The argument checks of nfd_block_causal_attn_fwd that do not need pointers
+ * (shape, capacity, support), in the same order and with the same codes. */
+int nfd_attn_check_args(nfd_dtype_t dtype, int B, int H, int F, int T, int D, int kv_frames,
+                        int q_frames);
+
+/* The tile schedule the forward would launch (Sec. 3.1: skipping the tiles of
+ * future frames IS the ~50 % saving the paper states). */
+typedef struct nfd_attn_plan {
+    int kernel;          /* 0 = general (fp32 / any D), 1 = bf16 matrix-core D=64 */
+    int block_m;         /* query rows per workgroup */
+    int block_n;         /* keys per inner tile */
+    int n_q_tiles;       /* query tiles per (b, h) */
+    int n_splits;        /* key splits per query tile (1 = no combine pass) */
+    int n_workgroups;    /* total workgroups of the main launch */
+    int64_t key_tiles_visited; /* sum over workgroups of key tiles actually visited */
+    int64_t key_tiles_dense;   /* the same count if no future tile were skipped */
+    size_t workspace_bytes;    /* scratch the split launch needs (0 if n_splits == 1) */
+} nfd_attn_plan_t;
+
+/* num_cus <= 0 selects 256; workspace_limit == 0 selects the default workspace. */
+int nfd_attn_plan(nfd_dtype_t dtype, int B, int H, int F, int T, int D, int kv_frames,
+                  int q_frames, int num_cus, size_t workspace_limit, nfd_attn_plan_t* plan);
+
+/* Visible (query, key) pairs per (b, h): T^2 (q_frames P + q_frames (q_frames + 1) / 2). */
+int64_t nfd_attn_visible_pairs(int T, int kv_frames, int q_frames);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* NFD_ATTN_H */

@@ -1,0 +1,189 @@
+"""ctypes binding of libnfd_attn.so: argument marshalling only.
+
+Function names mirror the C ABI (include/nfd_attn.h).  Tensors are passed as
+objects with ``data_ptr()`` (torch tensors) or as raw integer device addresses;
+PyTorch is used for device memory and streams only.  There is no fallback: if
+the shared library is missing or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libnfd_attn.so")
+
+NFD_BF16, NFD_FP32 = 0, 1
+NFD_OK, NFD_ERR_NULL, NFD_ERR_SHAPE, NFD_ERR_UNSUPPORTED = 0, -1, -2, -3
+NFD_ERR_CAPACITY, NFD_ERR_HIP, NFD_ERR_ALLOC = -4, -5, -6
+_ERR_NAMES = {
+    NFD_ERR_NULL: "NFD_ERR_NULL", NFD_ERR_SHAPE: "NFD_ERR_SHAPE", NFD_ERR_UNSUPPORTED: "NFD_ERR_UNSUPPORTED",
+    NFD_ERR_CAPACITY: "NFD_ERR_CAPACITY", NFD_ERR_HIP: "NFD_ERR_HIP", NFD_ERR_ALLOC: "NFD_ERR_ALLOC",
+}
+
+EXPORTS = (
+    "nfd_attn_create", "nfd_block_causal_attn_fwd", "nfd_kvcache_append", "nfd_attn_destroy",
+    "nfd_last_error", "nfd_attn_check_args", "nfd_attn_plan", "nfd_attn_visible_pairs",
+)
+
+
+class NfdError(RuntimeError):
+    def __init__(self, code, where, detail=""):
+        self.code = code
+        super().__init__("%s failed with %s (%d)%s" % (where, _ERR_NAMES.get(code, "?"), code,
+                                                      ": " + detail if detail else ""))
+
+
+class Plan(ctypes.Structure):
+    _fields_ = [
+        ("kernel", ctypes.c_int), ("block_m", ctypes.c_int), ("block_n", ctypes.c_int),
+        ("n_q_tiles", ctypes.c_int), ("n_splits", ctypes.c_int), ("n_workgroups", ctypes.c_int),
+        ("key_tiles_visited", ctypes.c_int64), ("key_tiles_dense", ctypes.c_int64),
+        ("workspace_bytes", ctypes.c_size_t),
+    ]
+
+    def as_dict(self):
+        return {n: getattr(self, n) for n, _ in self._fields_}
+
+
+_lib = None
+
+
+def lib():
+    """Load the shared library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(
+                "%s is missing: build it with `python -m paper_2506_01380_amd.build` "
+                "(there is no CPU or PyTorch fallback)" % LIB_PATH)
+        L = ctypes.CDLL(LIB_PATH)
+        vp, ci, cf = ctypes.c_void_p, ctypes.c_int, ctypes.c_float
+        L.nfd_attn_create.argtypes = [ctypes.POINTER(vp), ci, ci, ctypes.c_size_t]
+        L.nfd_attn_create.restype = ci
+        L.nfd_block_causal_attn_fwd.argtypes = [vp, vp, vp, vp, vp] + [ci] * 7 + [cf, vp]
+        L.nfd_block_causal_attn_fwd.restype = ci
+        L.nfd_kvcache_append.argtypes = [vp, vp, vp, vp, vp] + [ci] * 7 + [vp]
+        L.nfd_kvcache_append.restype = ci
+        L.nfd_attn_destroy.argtypes = [vp]
+        L.nfd_attn_destroy.restype = ci
+        L.nfd_last_error.argtypes = [vp]
+        L.nfd_last_error.restype = ctypes.c_char_p
+        L.nfd_attn_check_args.argtypes = [ci] * 8
+        L.nfd_attn_check_args.restype = ci
+        L.nfd_attn_plan.argtypes = [ci] * 9 + [ctypes.c_size_t, ctypes.POINTER(Plan)]
+        L.nfd_attn_plan.restype = ci
+        L.nfd_attn_visible_pairs.argtypes = [ci] * 3
+        L.nfd_attn_visible_pairs.restype = ctypes.c_int64
+        _lib = L
+    return _lib
+
+
+def _addr(x):
+    if x is None:
+        return None
+    if hasattr(x, "data_ptr"):
+        return x.data_ptr()
+    return int(x)
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    if hasattr(stream, "cuda_stream"):
+        return stream.cuda_stream
+    return int(stream)
+
+
+def _check(rc, where, h=None):
+    if rc != NFD_OK:
+        detail = ""
+        if h:
+            detail = (lib().nfd_last_error(h) or b"").decode()
+        raise NfdError(rc, where, detail)
+
+
+def nfd_attn_create(dtype=NFD_BF16, device=0, workspace_bytes=0):
+    h = ctypes.c_void_p()
+    _check(lib().nfd_attn_create(ctypes.byref(h), dtype, device, workspace_bytes), "nfd_attn_create")
+    return h
+
+
+def nfd_block_causal_attn_fwd(h, q, k, v, out, B, H, F, T, D, kv_frames, q_frames, scale=0.0, stream=None):
+    rc = lib().nfd_block_causal_attn_fwd(h, _addr(q), _addr(k), _addr(v), _addr(out), B, H, F, T, D,
+                                         kv_frames, q_frames, scale, _stream(stream))
+    _check(rc, "nfd_block_causal_attn_fwd", h)
+
+
+def nfd_kvcache_append(h, k_cache, v_cache, k_new, v_new, B, H, F, T, D, frame_pos, n_frames, stream=None):
+    rc = lib().nfd_kvcache_append(h, _addr(k_cache), _addr(v_cache), _addr(k_new), _addr(v_new), B, H, F, T, D,
+                                  frame_pos, n_frames, _stream(stream))
+    _check(rc, "nfd_kvcache_append", h)
+
+
+def nfd_attn_destroy(h):
+    _check(lib().nfd_attn_destroy(h), "nfd_attn_destroy")
+
+
+def nfd_attn_check_args(dtype, B, H, F, T, D, kv_frames, q_frames):
+    return lib().nfd_attn_check_args(dtype, B, H, F, T, D, kv_frames, q_frames)
+
+
+def nfd_attn_plan(dtype, B, H, F, T, D, kv_frames, q_frames, num_cus=0, workspace_limit=0):
+    pl = Plan()
+    _check(lib().nfd_attn_plan(dtype, B, H, F, T, D, kv_frames, q_frames, num_cus, workspace_limit,
+                               ctypes.byref(pl)), "nfd_attn_plan")
+    return pl.as_dict()
+
+
+def nfd_attn_visible_pairs(T, kv_frames, q_frames):
+    return lib().nfd_attn_visible_pairs(T, kv_frames, q_frames)
+
+
+def unmasked_flops(B, H, D, T, kv_frames, q_frames):
+    """FLOPs of the visible (query, key) pairs only: 4*D per pair (QK^T and PV)."""
+    return 4 * D * nfd_attn_visible_pairs(T, kv_frames, q_frames) * B * H
+
+
+class Attention:
+    """Convenience holder of one handle; shapes are read from the tensors.
+
+    q: [B,H,q_frames*T,D]; k, v: [B,H,F*T,D] (the cache, or the full sequence)."""
+
+    def __init__(self, dtype="bf16", device=0, workspace_bytes=0):
+        self.dtype = {"bf16": NFD_BF16, "fp32": NFD_FP32}[dtype]
+        self.h = nfd_attn_create(self.dtype, device, workspace_bytes)
+
+    def forward(self, q, k, v, T, kv_frames=None, q_frames=None, out=None, scale=0.0, stream=None):
+        import torch
+        B, H, Sq, D = q.shape
+        F = k.shape[2] // T
+        q_frames = Sq // T if q_frames is None else q_frames
+        kv_frames = F if kv_frames is None else kv_frames
+        want = torch.bfloat16 if self.dtype == NFD_BF16 else torch.float32
+        for t in (q, k, v):
+            if t.dtype != want or not t.is_contiguous() or not t.is_cuda:
+                raise ValueError("tensors must be contiguous CUDA tensors of the handle's dtype")
+        if Sq != q_frames * T or k.shape != v.shape or k.shape[2] != F * T or k.shape[:2] != (B, H) or k.shape[3] != D:
+            raise ValueError("shape mismatch")
+        if out is None:
+            out = torch.empty_like(q)
+        nfd_block_causal_attn_fwd(self.h, q, k, v, out, B, H, F, T, D, kv_frames, q_frames, scale, stream)
+        return out
+
+    def append(self, k_cache, v_cache, k_new, v_new, T, frame_pos, stream=None):
+        B, H, Sc, D = k_cache.shape
+        n_frames = k_new.shape[2] // T
+        nfd_kvcache_append(self.h, k_cache, v_cache, k_new, v_new, B, H, Sc // T, T, D, frame_pos, n_frames, stream)
+
+    def close(self):
+        if self.h is not None:
+            nfd_attn_destroy(self.h)
+            self.h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

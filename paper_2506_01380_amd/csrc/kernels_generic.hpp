@@ -1,0 +1,117 @@
+// General forward kernel: any T, any D <= 256, fp32 or bf16 storage, fp32 arithmetic.
+// One wavefront owns one query row and walks the visible keys 64 at a time with an
+// online softmax.  It is the fp32 path of the library and the fallback for head
+// widths the matrix-core kernel is not built for; it is not tuned.
+#pragma once
+#include "nfd_common.hpp"
+
+namespace nfd {
+
+template <typename T> __device__ __forceinline__ float to_f32(T x);
+template <> __device__ __forceinline__ float to_f32<float>(float x) { return x; }
+template <> __device__ __forceinline__ float to_f32<__bf16>(__bf16 x) { return (float)x; }
+template <typename T> __device__ __forceinline__ T from_f32(float x);
+template <> __device__ __forceinline__ float from_f32<float>(float x) { return x; }
+template <> __device__ __forceinline__ __bf16 from_f32<__bf16>(float x) { return (__bf16)x; }  // RNE
+
+__device__ __forceinline__ float wave_max(float x) {
+    for (int o = 32; o > 0; o >>= 1) x = fmaxf(x, __shfl_xor(x, o));
+    return x;
+}
+__device__ __forceinline__ float wave_sum(float x) {
+    for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o);
+    return x;
+}
+
+constexpr int kGenericWaves = 4;
+constexpr int kGenericMaxD = 256;
+
+template <typename T>
+__global__ void __launch_bounds__(kGenericWaves * 64)
+attn_fwd_generic(FwdParams p) {
+    __shared__ float q_s[kGenericWaves][kGenericMaxD];
+    __shared__ float p_s[kGenericWaves][64];
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int64_t row_id = (int64_t)blockIdx.x * kGenericWaves + w;  // over BH * Sq
+    if (row_id >= (int64_t)p.BH * p.Sq) return;                      // whole wave exits together
+    const int bh = (int)(row_id / p.Sq), i = (int)(row_id % p.Sq);
+    const int D = p.D;
+    const T* q = (const T*)p.q + ((int64_t)bh * p.Sq + i) * D;
+    const T* k = (const T*)p.k + (int64_t)bh * p.Scap * D;
+    const T* v = (const T*)p.v + (int64_t)bh * p.Scap * D;
+    T* out = (T*)p.out + ((int64_t)bh * p.Sq + i) * D;
+
+    for (int d = lane; d < D; d += 64) q_s[w][d] = to_f32<T>(q[d]);
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): q_s visible within the wave
+
+    const int kmax = kmax_of_row(i, p.T, p.P);  // <= Sk by construction
+    float m = kNegBig, l = 0.f;
+    float acc[kGenericMaxD / 64] = {0.f, 0.f, 0.f, 0.f};
+
+    for (int j0 = 0; j0 < kmax; j0 += 64) {
+        const int j = j0 + lane;
+        float s = -INFINITY;
+        if (j < kmax) {
+            const T* kr = k + (int64_t)j * D;
+            float a = 0.f;
+            for (int d = 0; d < D; ++d) a = fmaf(q_s[w][d], to_f32<T>(kr[d]), a);
+            s = a * p.scale_log2e;  // log2 units
+        }
+        const float m_new = fmaxf(m, wave_max(s));
+        const float alpha = exp2f(m - m_new);
+        const float pj = exp2f(s - m_new);  // 0 for masked lanes
+        l = l * alpha + wave_sum(pj);
+        m = m_new;
+        p_s[w][lane] = pj;
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_s_waitcnt(0xc07f);
+        const int nj = min(64, kmax - j0);
+#pragma unroll
+        for (int c = 0; c < kGenericMaxD / 64; ++c) {
+            const int d = lane + 64 * c;
+            if (d < D) {
+                float a = acc[c] * alpha;
+                for (int jj = 0; jj < nj; ++jj) a = fmaf(p_s[w][jj], to_f32<T>(v[(int64_t)(j0 + jj) * D + d]), a);
+                acc[c] = a;
+            }
+        }
+        __builtin_amdgcn_wave_barrier();
+    }
+    const float inv = 1.0f / l;
+#pragma unroll
+    for (int c = 0; c < kGenericMaxD / 64; ++c) {
+        const int d = lane + 64 * c;
+        if (d < D) out[d] = from_f32<T>(acc[c] * inv);
+    }
+}
+
+// Copy n_frames frames of every head into the cache at frame_pos (Appendix B, KV caching).
+// One 16-byte vector per thread-iteration; row_vecs = T*D*sizeof(elem)/16 per frame.
+__global__ void __launch_bounds__(256)
+kvcache_append_vec16(u32x4* __restrict__ kc, u32x4* __restrict__ vc, const u32x4* __restrict__ kn,
+                     const u32x4* __restrict__ vn, int64_t head_vecs_cache, int64_t head_vecs_new,
+                     int64_t offset_vecs, int64_t total_vecs) {
+    for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total_vecs;
+         idx += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t bh = idx / head_vecs_new, r = idx % head_vecs_new;
+        const int64_t dst = bh * head_vecs_cache + offset_vecs + r;
+        kc[dst] = kn[idx];
+        vc[dst] = vn[idx];
+    }
+}
+// Element-granular variant for shapes whose frame size is not a multiple of 16 bytes.
+template <typename E>
+__global__ void __launch_bounds__(256)
+kvcache_append_elem(E* __restrict__ kc, E* __restrict__ vc, const E* __restrict__ kn, const E* __restrict__ vn,
+                    int64_t head_cache, int64_t head_new, int64_t offset, int64_t total) {
+    for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total;
+         idx += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t bh = idx / head_new, r = idx % head_new;
+        const int64_t dst = bh * head_cache + offset + r;
+        kc[dst] = kn[idx];
+        vc[dst] = vn[idx];
+    }
+}
+
+}  // namespace nfd

@@ -1,0 +1,247 @@
+// Host side of the C ABI declared in include/nfd_attn.h: argument checks, tile schedule,
+// kernel selection and launches.  No allocation and no host synchronisation happens in
+// the forward or append calls.
+#include "../../include/nfd_attn.h"
+
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdio>
+#include <cstdlib>
+#include <new>
+#include <string>
+
+#include "kernels_generic.hpp"
+#include "kernels_mfma.hpp"
+
+struct nfd_attn {
+    nfd_dtype_t dtype;
+    int device;
+    int num_cus;
+    void* workspace;
+    size_t workspace_bytes;
+    std::string err;
+};
+
+namespace {
+
+constexpr size_t kDefaultWorkspace = (size_t)128 << 20;
+constexpr int kMfmaWaves = 4;
+
+int fail(nfd_attn_t* h, int code, const std::string& msg) {
+    if (h) h->err = msg;
+    return code;
+}
+
+int check_hip(nfd_attn_t* h, hipError_t e, const char* what) {
+    if (e == hipSuccess) return NFD_OK;
+    return fail(h, NFD_ERR_HIP, std::string(what) + ": " + hipGetErrorString(e));
+}
+
+size_t elem_size(nfd_dtype_t dt) { return dt == NFD_BF16 ? 2 : 4; }
+
+// Largest key bound of a block of query rows [r0, r0 + bm) (Sec. 3.1: a row sees all
+// frames up to and including its own).
+int64_t kmax_rows(int64_t r_last, int T, int P) { return ((int64_t)P + r_last / T + 1) * T; }
+
+}  // namespace
+
+extern "C" {
+
+int64_t nfd_attn_visible_pairs(int T, int kv_frames, int q_frames) {
+    if (T < 1 || q_frames < 1 || kv_frames < q_frames) return -1;
+    const int64_t P = (int64_t)kv_frames - q_frames, n = q_frames;
+    return (int64_t)T * T * (n * P + n * (n + 1) / 2);
+}
+
+int nfd_attn_check_args(nfd_dtype_t dtype, int B, int H, int F, int T, int D, int kv_frames, int q_frames) {
+    if (B < 1 || H < 1 || F < 1 || T < 1 || D < 1 || q_frames < 1 || kv_frames < 1) return NFD_ERR_SHAPE;
+    if (q_frames > kv_frames) return NFD_ERR_SHAPE;
+    if (kv_frames > F) return NFD_ERR_CAPACITY;
+    if (dtype != NFD_BF16 && dtype != NFD_FP32) return NFD_ERR_UNSUPPORTED;
+    if (D > nfd::kGenericMaxD) return NFD_ERR_UNSUPPORTED;
+    // 32-bit row indexing inside the kernels
+    if ((int64_t)F * T > (int64_t)1 << 30 || (int64_t)B * H > (int64_t)1 << 24) return NFD_ERR_UNSUPPORTED;
+    return NFD_OK;
+}
+
+int nfd_attn_plan(nfd_dtype_t dtype, int B, int H, int F, int T, int D, int kv_frames, int q_frames,
+                  int num_cus, size_t workspace_limit, nfd_attn_plan_t* plan) {
+    if (!plan) return NFD_ERR_NULL;
+    const int rc = nfd_attn_check_args(dtype, B, H, F, T, D, kv_frames, q_frames);
+    if (rc != NFD_OK) return rc;
+    if (num_cus <= 0) num_cus = 256;
+    if (workspace_limit == 0) workspace_limit = kDefaultWorkspace;
+    const int64_t BH = (int64_t)B * H, Sq = (int64_t)q_frames * T;
+    const int P = kv_frames - q_frames;
+    nfd_attn_plan_t pl{};
+    if (dtype == NFD_BF16 && D == nfd::mfma::kD) {
+        pl.kernel = 1;
+        pl.block_m = kMfmaWaves * 64;
+        pl.block_n = nfd::mfma::kBN;
+        pl.n_q_tiles = (int)((Sq + pl.block_m - 1) / pl.block_m);
+        int64_t visited = 0, max_tiles = 0;
+        for (int qt = 0; qt < pl.n_q_tiles; ++qt) {
+            const int64_t r_last = std::min<int64_t>((int64_t)(qt + 1) * pl.block_m, Sq) - 1;
+            const int64_t nt = (kmax_rows(r_last, T, P) + pl.block_n - 1) / pl.block_n;
+            visited += nt;
+            max_tiles = std::max(max_tiles, nt);
+        }
+        // Key splits: only when the query tiles alone cannot fill the chip (cached forms).
+        const int64_t slots = (int64_t)num_cus * 2, base = BH * pl.n_q_tiles;
+        int splits = 1;
+        if (base < slots) {
+            splits = (int)((slots + base - 1) / base);
+            splits = (int)std::min<int64_t>(splits, std::max<int64_t>(1, max_tiles / 4));
+            const size_t per_split = (size_t)(BH * Sq) * (nfd::mfma::kD + 2) * sizeof(float);
+            while (splits > 1 && per_split * splits > workspace_limit) --splits;
+        }
+        pl.n_splits = splits;
+        pl.n_workgroups = (int)(8 * ((BH + 7) / 8) * pl.n_q_tiles * splits);
+        pl.key_tiles_visited = visited * BH;
+        pl.key_tiles_dense = (int64_t)pl.n_q_tiles * (((int64_t)kv_frames * T + pl.block_n - 1) / pl.block_n) * BH;
+        pl.workspace_bytes = splits > 1 ? (size_t)(BH * Sq) * splits * (nfd::mfma::kD + 2) * sizeof(float) : 0;
+    } else {
+        pl.kernel = 0;
+        pl.block_m = nfd::kGenericWaves;  // one row per wavefront
+        pl.block_n = 64;
+        pl.n_q_tiles = (int)((Sq + pl.block_m - 1) / pl.block_m);
+        pl.n_splits = 1;
+        pl.n_workgroups = (int)((BH * Sq + nfd::kGenericWaves - 1) / nfd::kGenericWaves);
+        int64_t visited = 0;
+        for (int64_t i = 0; i < Sq; ++i) visited += (kmax_rows(i, T, P) + 63) / 64;
+        pl.key_tiles_visited = visited * BH;
+        pl.key_tiles_dense = Sq * (((int64_t)kv_frames * T + 63) / 64) * BH;
+        pl.workspace_bytes = 0;
+    }
+    *plan = pl;
+    return NFD_OK;
+}
+
+int nfd_attn_create(nfd_attn_t** out, nfd_dtype_t dtype, int device, size_t workspace_bytes) {
+    if (!out) return NFD_ERR_NULL;
+    *out = nullptr;
+    if (dtype != NFD_BF16 && dtype != NFD_FP32) return NFD_ERR_UNSUPPORTED;
+    nfd_attn_t* h = new (std::nothrow) nfd_attn();
+    if (!h) return NFD_ERR_ALLOC;
+    h->dtype = dtype;
+    h->device = device;
+    h->workspace = nullptr;
+    h->workspace_bytes = workspace_bytes ? workspace_bytes : kDefaultWorkspace;
+    int prev = 0;
+    hipError_t e = hipGetDevice(&prev);
+    if (e == hipSuccess) e = hipSetDevice(device);
+    hipDeviceProp_t prop;
+    if (e == hipSuccess) e = hipGetDeviceProperties(&prop, device);
+    if (e != hipSuccess) {
+        delete h;
+        return NFD_ERR_HIP;
+    }
+    h->num_cus = prop.multiProcessorCount;
+    const std::string arch = prop.gcnArchName;
+    if (arch.rfind("gfx950", 0) != 0) {
+        (void)hipSetDevice(prev);
+        delete h;
+        return NFD_ERR_UNSUPPORTED;  // the kernels are written for CDNA4 only
+    }
+    e = hipMalloc(&h->workspace, h->workspace_bytes);
+    (void)hipSetDevice(prev);
+    if (e != hipSuccess) {
+        delete h;
+        return NFD_ERR_ALLOC;
+    }
+    *out = h;
+    return NFD_OK;
+}
+
+int nfd_attn_destroy(nfd_attn_t* h) {
+    if (!h) return NFD_OK;
+    hipError_t e = hipSuccess;
+    if (h->workspace) e = hipFree(h->workspace);
+    delete h;
+    return e == hipSuccess ? NFD_OK : NFD_ERR_HIP;
+}
+
+const char* nfd_last_error(const nfd_attn_t* h) { return h ? h->err.c_str() : "null handle"; }
+
+int nfd_block_causal_attn_fwd(nfd_attn_t* h, const void* q, const void* k, const void* v, void* out, int B,
+                              int H, int F, int T, int D, int kv_frames, int q_frames, float scale,
+                              void* stream) {
+    if (!h) return NFD_ERR_NULL;
+    if (!q || !k || !v || !out) return fail(h, NFD_ERR_NULL, "q, k, v and out must be non-null");
+    nfd_attn_plan_t pl;
+    const int rc = nfd_attn_plan(h->dtype, B, H, F, T, D, kv_frames, q_frames, h->num_cus, h->workspace_bytes, &pl);
+    if (rc != NFD_OK) return fail(h, rc, "invalid shape arguments");
+    if (!(scale > 0.f)) scale = 1.0f / std::sqrt((float)D);
+
+    nfd::FwdParams p{};
+    p.q = q; p.k = k; p.v = v; p.out = out;
+    p.BH = B * H;
+    p.Sq = q_frames * T;
+    p.Sk = kv_frames * T;
+    p.Scap = F * T;
+    p.T = T;
+    p.P = kv_frames - q_frames;
+    p.D = D;
+    p.n_q_tiles = pl.n_q_tiles;
+    p.n_splits = pl.n_splits;
+    p.scale_log2e = scale * nfd::kLog2e;
+    if (pl.n_splits > 1) {
+        p.part_o = (float*)h->workspace;
+        p.part_ml = p.part_o + (size_t)p.BH * pl.n_splits * p.Sq * nfd::mfma::kD;
+    }
+    hipStream_t st = (hipStream_t)stream;
+
+    if (pl.kernel == 1) {
+        hipLaunchKernelGGL(nfd::mfma::attn_fwd_bf16_d64<kMfmaWaves>, dim3(pl.n_workgroups), dim3(kMfmaWaves * 64), 0,
+                           st, p);
+        if (pl.n_splits > 1) {
+            const int64_t total = (int64_t)p.BH * p.Sq * (nfd::mfma::kD / 4);
+            hipLaunchKernelGGL(nfd::mfma::attn_combine_d64, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, p);
+        }
+    } else if (h->dtype == NFD_FP32) {
+        hipLaunchKernelGGL(nfd::attn_fwd_generic<float>, dim3(pl.n_workgroups), dim3(nfd::kGenericWaves * 64), 0, st, p);
+    } else {
+        hipLaunchKernelGGL(nfd::attn_fwd_generic<__bf16>, dim3(pl.n_workgroups), dim3(nfd::kGenericWaves * 64), 0, st, p);
+    }
+    return check_hip(h, hipGetLastError(), "attention launch");
+}
+
+int nfd_kvcache_append(nfd_attn_t* h, void* k_cache, void* v_cache, const void* k_new, const void* v_new, int B,
+                       int H, int F, int T, int D, int frame_pos, int n_frames, void* stream) {
+    if (!h) return NFD_ERR_NULL;
+    if (!k_cache || !v_cache || !k_new || !v_new) return fail(h, NFD_ERR_NULL, "cache and new tensors must be non-null");
+    if (B < 1 || H < 1 || F < 1 || T < 1 || D < 1 || n_frames < 0 || frame_pos < 0)
+        return fail(h, NFD_ERR_SHAPE, "invalid shape arguments");
+    if ((int64_t)frame_pos + n_frames > F) return fail(h, NFD_ERR_CAPACITY, "frame_pos + n_frames exceeds the cache capacity F");
+    if (n_frames == 0) return NFD_OK;
+    const size_t es = elem_size(h->dtype);
+    const int64_t frame_elems = (int64_t)T * D;
+    const int64_t BH = (int64_t)B * H;
+    hipStream_t st = (hipStream_t)stream;
+    const bool vec = (frame_elems * es) % 16 == 0 && ((uintptr_t)k_cache % 16 == 0) && ((uintptr_t)v_cache % 16 == 0) &&
+                     ((uintptr_t)k_new % 16 == 0) && ((uintptr_t)v_new % 16 == 0);
+    if (vec) {
+        const int64_t fv = frame_elems * es / 16;
+        const int64_t total = BH * n_frames * fv;
+        const unsigned grid = (unsigned)std::min<int64_t>((total + 255) / 256, (int64_t)h->num_cus * 16);
+        hipLaunchKernelGGL(nfd::kvcache_append_vec16, dim3(grid), dim3(256), 0, st, (nfd::u32x4*)k_cache,
+                           (nfd::u32x4*)v_cache, (const nfd::u32x4*)k_new, (const nfd::u32x4*)v_new, (int64_t)F * fv,
+                           (int64_t)n_frames * fv, (int64_t)frame_pos * fv, total);
+    } else {
+        const int64_t total = BH * n_frames * frame_elems;
+        const unsigned grid = (unsigned)std::min<int64_t>((total + 255) / 256, (int64_t)h->num_cus * 16);
+        if (es == 2)
+            hipLaunchKernelGGL(nfd::kvcache_append_elem<uint16_t>, dim3(grid), dim3(256), 0, st, (uint16_t*)k_cache,
+                               (uint16_t*)v_cache, (const uint16_t*)k_new, (const uint16_t*)v_new, (int64_t)F * frame_elems,
+                               (int64_t)n_frames * frame_elems, (int64_t)frame_pos * frame_elems, total);
+        else
+            hipLaunchKernelGGL(nfd::kvcache_append_elem<uint32_t>, dim3(grid), dim3(256), 0, st, (uint32_t*)k_cache,
+                               (uint32_t*)v_cache, (const uint32_t*)k_new, (const uint32_t*)v_new, (int64_t)F * frame_elems,
+                               (int64_t)n_frames * frame_elems, (int64_t)frame_pos * frame_elems, total);
+    }
+    return check_hip(h, hipGetLastError(), "kvcache append launch");
+}
+
+}  // extern "C"

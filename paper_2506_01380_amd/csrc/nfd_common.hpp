@@ -1,0 +1,46 @@
+// Shared device-side vocabulary of the gfx950 attention kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace nfd {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+
+constexpr float kLog2e = 1.4426950408889634f;
+// Running maxima start at a large finite negative so that (m_old - m_new) is never inf - inf.
+constexpr float kNegBig = -1.0e30f;
+
+// Launch geometry and tensor description shared by every forward kernel.
+// Mask (Sec. 3.1, block-wise causal attention): query row i sees keys
+// j < kmax(i) = (P + i / T + 1) * T, i.e. all frames up to and including its own.
+struct FwdParams {
+    const void* q;      // [BH, Sq, D]
+    const void* k;      // [BH, Scap, D]
+    const void* v;      // [BH, Scap, D]
+    void* out;          // [BH, Sq, D]
+    float* part_o;      // [BH, n_splits, Sq, D] un-normalised partial outputs (split launches)
+    float* part_ml;     // [BH, n_splits, Sq, 2]  (running max in log2 units, running sum)
+    int BH;             // B * H
+    int Sq;             // q_frames * T
+    int Sk;             // kv_frames * T
+    int Scap;           // F * T (head stride of k, v in rows)
+    int T;              // tokens per frame
+    int P;              // kv_frames - q_frames
+    int D;
+    int n_q_tiles;      // query tiles per head
+    int n_splits;       // key splits per query tile
+    float scale_log2e;  // softmax scale * log2(e)
+};
+
+__device__ __forceinline__ int kmax_of_row(int row, int T, int P) { return (P + row / T + 1) * T; }
+
+}  // namespace nfd

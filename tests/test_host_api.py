@@ -1,0 +1,83 @@
+"""CPU-side checks of the C-ABI library: it loads, exports what the header declares,
+validates arguments with the documented codes, and plans a tile schedule that skips
+future frames.  No compute call is made (there is no GPU here)."""
+import os
+import re
+
+import pytest
+
+from oracle import nfd_oracle as orc
+from paper_2506_01380_amd import binding as nb
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "nfd_attn.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(nfd_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = declared_functions()
+    assert {"nfd_attn_create", "nfd_block_causal_attn_fwd", "nfd_kvcache_append", "nfd_attn_destroy"} <= set(names)
+    L = nb.lib()
+    for n in names:
+        assert hasattr(L, n), n
+    assert set(names) == set(nb.EXPORTS)
+
+
+@pytest.mark.parametrize("args,code", [
+    (dict(B=1, H=2, F=4, T=16, D=64, kv_frames=4, q_frames=4), nb.NFD_OK),
+    (dict(B=0, H=2, F=4, T=16, D=64, kv_frames=4, q_frames=4), nb.NFD_ERR_SHAPE),
+    (dict(B=1, H=2, F=4, T=0, D=64, kv_frames=4, q_frames=4), nb.NFD_ERR_SHAPE),
+    (dict(B=1, H=2, F=4, T=16, D=64, kv_frames=4, q_frames=0), nb.NFD_ERR_SHAPE),
+    (dict(B=1, H=2, F=4, T=16, D=64, kv_frames=3, q_frames=4), nb.NFD_ERR_SHAPE),
+    (dict(B=1, H=2, F=4, T=16, D=64, kv_frames=5, q_frames=4), nb.NFD_ERR_CAPACITY),
+    (dict(B=1, H=2, F=4, T=16, D=512, kv_frames=4, q_frames=4), nb.NFD_ERR_UNSUPPORTED),
+])
+def test_check_args_codes(args, code):
+    assert nb.nfd_attn_check_args(nb.NFD_BF16, **args) == code
+
+
+def test_bad_dtype_is_unsupported():
+    assert nb.nfd_attn_check_args(7, 1, 1, 1, 1, 64, 1, 1) == nb.NFD_ERR_UNSUPPORTED
+
+
+@pytest.mark.parametrize("T,kvf,qf", [(16, 4, 4), (3, 5, 2), (336, 33, 1), (7, 9, 9)])
+def test_visible_pairs_matches_enumeration(T, kvf, qf):
+    assert nb.nfd_attn_visible_pairs(T, kvf, qf) == orc.visible_pairs(T, kvf, qf)
+
+
+def test_plan_training_form_skips_future_tiles():
+    # Sec. 3.1: about half of the dense attention cost
+    pl = nb.nfd_attn_plan(nb.NFD_BF16, 4, 16, 16, 336, 64, 16, 16)
+    assert pl["kernel"] == 1 and pl["n_splits"] == 1
+    frac = pl["key_tiles_visited"] / pl["key_tiles_dense"]
+    assert 0.5 < frac < 0.60
+    pl = nb.nfd_attn_plan(nb.NFD_BF16, 2, 16, 64, 576, 64, 64, 64)
+    assert 0.5 < pl["key_tiles_visited"] / pl["key_tiles_dense"] < 0.53
+
+
+def test_plan_cached_forms_split_keys_and_fit_workspace():
+    pl = nb.nfd_attn_plan(nb.NFD_BF16, 1, 16, 40, 336, 64, 33, 1)
+    assert pl["n_splits"] > 1 and pl["workspace_bytes"] <= 128 << 20
+    assert pl["workspace_bytes"] == 16 * 336 * pl["n_splits"] * 66 * 4
+    small = nb.nfd_attn_plan(nb.NFD_BF16, 1, 16, 40, 336, 64, 33, 1, 256, 3 * 16 * 336 * 66 * 4)
+    assert small["n_splits"] == 3
+    none = nb.nfd_attn_plan(nb.NFD_BF16, 1, 16, 40, 336, 64, 33, 1, 256, 1000)
+    assert none["n_splits"] == 1 and none["workspace_bytes"] == 0
+
+
+def test_plan_general_kernel_for_fp32_and_other_widths():
+    assert nb.nfd_attn_plan(nb.NFD_FP32, 1, 2, 4, 16, 64, 4, 4)["kernel"] == 0
+    assert nb.nfd_attn_plan(nb.NFD_BF16, 1, 2, 4, 16, 128, 4, 4)["kernel"] == 0
+
+
+def test_create_without_gpu_reports_an_error_code():
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is present")
+    with pytest.raises(nb.NfdError) as e:
+        nb.nfd_attn_create(nb.NFD_BF16, 0)
+    assert e.value.code in (nb.NFD_ERR_HIP, nb.NFD_ERR_ALLOC)
