@@ -36,6 +36,12 @@ __device__ __forceinline__ s16x4 lds_read_tr(const __bf16* p) {
     return __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p));
 }
 
+// Wait for every outstanding vector-memory load of this wavefront.  Used once after the Q
+// fragments are fetched: otherwise the compiler, unable to prove they have landed on every
+// path into the main loop, guards each matrix instruction that reads them with an in-order
+// vmcnt wait, and those waits would drain the K/V prefetch issued just before.
+__device__ __forceinline__ void wait_vmem_all() { __builtin_amdgcn_s_waitcnt(0x0F70); }
+
 template <int NW>
 struct Smem {
     __bf16 k[2][kBN * kKStr];
@@ -147,6 +153,7 @@ attn_fwd_bf16_d64(FwdParams p) {
         load_tile(t_begin);
         store_tile(0);
     }
+    wait_vmem_all();
     __syncthreads();
 
     // lane-constant LDS offsets
@@ -154,17 +161,32 @@ attn_fwd_bf16_d64(FwdParams p) {
     const int s16 = lane & 15, dblk = (lane >> 4) & 1;
     const int v_off = (4 * h + (s16 >> 2)) * kVStr + 16 * dblk + 4 * (s16 & 3);  // + (32kb+16g [+8]) rows, + 32*dt cols
 
+#ifdef NFD_STAGE_TIMING
+    unsigned long long tsum[5] = {0, 0, 0, 0, 0}, tc0, tc1;
+#define NFD_TICK(i) { __builtin_amdgcn_s_waitcnt(0); tc1 = __builtin_readcyclecounter(); tsum[i] += tc1 - tc0; tc0 = tc1; }
+    tc0 = __builtin_readcyclecounter();
+#else
+#define NFD_TICK(i)
+#endif
     for (int t = t_begin; t < t_end; ++t) {
         const int buf = (t - t_begin) & 1;
         const int j0 = t * kBN;
         const bool has_next = t + 1 < t_end;
         if (has_next) load_tile(t + 1);
+        NFD_TICK(0)
 
         if (wave_active && j0 < kmax_wave) {
             const __bf16* ks_ = sm.k[buf];
             const __bf16* vs_ = sm.v[buf];
-            // ---- S^T = K . Q^T ----------------------------------------------------------------
+            // ---- S^T = K . Q^T: all eight K fragments are requested before the first product so the
+            // LDS latency is paid once per tile, not once per fragment ------------------------------
             f32x16 s_acc[2][2];  // [kb][qt]
+            bf16x8 kf[2][4];
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks) kf[kb][ks] = lds_read_b128(ks_ + k_off + 32 * kb * kKStr + 16 * ks);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb) {
 #pragma unroll
@@ -173,12 +195,28 @@ attn_fwd_bf16_d64(FwdParams p) {
                     for (int r = 0; r < 16; ++r) s_acc[kb][qt][r] = 0.f;
 #pragma unroll
                 for (int ks = 0; ks < 4; ++ks) {
-                    const bf16x8 a = lds_read_b128(ks_ + k_off + 32 * kb * kKStr + 16 * ks);
 #pragma unroll
                     for (int qt = 0; qt < 2; ++qt)
-                        s_acc[kb][qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[qt][ks], s_acc[kb][qt], 0, 0, 0);
+                        s_acc[kb][qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kb][ks], qf[qt][ks], s_acc[kb][qt], 0, 0, 0);
                 }
             }
+            // V^T fragments for the second product are requested now and land during the softmax.
+            bf16x8 vf[2][2][2];  // [kb][g][dt]
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int g = 0; g < 2; ++g)
+#pragma unroll
+                    for (int dt = 0; dt < 2; ++dt) {
+                        const __bf16* vp = vs_ + v_off + (32 * kb + 16 * g) * kVStr + 32 * dt;
+                        const s16x4 lo = lds_read_tr(vp);
+                        const s16x4 hi = lds_read_tr(vp + 8 * kVStr);
+                        typedef __attribute__((ext_vector_type(8))) short s16x8;
+                        const s16x8 av = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                        vf[kb][g][dt] = __builtin_bit_cast(bf16x8, av);
+                    }
+            __builtin_amdgcn_sched_barrier(0);
+            NFD_TICK(1)
             // ---- mask (only tiles that cross some row's bound) ---------------------------------
             if (j0 + kBN > kmin_wave) {
 #pragma unroll
@@ -240,28 +278,32 @@ attn_fwd_bf16_d64(FwdParams p) {
                     }
                 l_sum[qt] = l;
             }
+            NFD_TICK(2)
             // ---- O^T += V^T . P^T -----------------------------------------------------------------
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
                 for (int g = 0; g < 2; ++g)
 #pragma unroll
-                    for (int dt = 0; dt < 2; ++dt) {
-                        const __bf16* vp = vs_ + v_off + (32 * kb + 16 * g) * kVStr + 32 * dt;
-                        const s16x4 lo = lds_read_tr(vp);
-                        const s16x4 hi = lds_read_tr(vp + 8 * kVStr);
-                        typedef __attribute__((ext_vector_type(8))) short s16x8;
-                        const s16x8 av = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-                        const bf16x8 a = __builtin_bit_cast(bf16x8, av);
+                    for (int dt = 0; dt < 2; ++dt)
 #pragma unroll
                         for (int qt = 0; qt < 2; ++qt)
-                            o_acc[dt][qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[kb][g][qt], o_acc[dt][qt], 0, 0, 0);
-                    }
+                            o_acc[dt][qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[kb][g][dt], pf[kb][g][qt], o_acc[dt][qt], 0, 0, 0);
         }
 
+        NFD_TICK(3)
         if (has_next) store_tile(buf ^ 1);
         __syncthreads();
+        NFD_TICK(4)
     }
+#ifdef NFD_STAGE_TIMING
+    if (p.timing && lane == 0) {
+        unsigned long long* o = p.timing + ((size_t)blockIdx.x * NW + wv) * 8;
+        for (int i = 0; i < 5; ++i) o[i] = tsum[i];
+        o[5] = (unsigned long long)(t_end - t_begin);
+    }
+#endif
 
     // ---- epilogue -----------------------------------------------------------------------------
     if (!wave_active) return;
@@ -297,6 +339,367 @@ attn_fwd_bf16_d64(FwdParams p) {
                 *(f32x2*)(p.part_ml + prow * 2) = ml;
             }
         }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Ping-pong variant: 8 wavefronts = two groups of 4.  Wavefront w of group A and wavefront w of
+// group B own the SAME 64 query rows and share a SIMD; group A takes the even key tiles of the
+// workgroup's range, group B the odd ones, each with its own accumulators, and the two are
+// merged through LDS at the end.  Time is cut into barrier-delimited intervals; in every
+// interval one group runs its matrix-core stage (P.V of its previous tile, then K.Q^T of its
+// next tile) while the other runs its softmax stage on the vector ALU, so the MFMA pipe and
+// the VALU of a SIMD are busy at the same time instead of taking turns.
+//
+// Softmax is optimistic: P is formed against the reference max of earlier tiles without first
+// looking at this tile's max; only if a lane's tile sum reaches kOptimisticLimit (which also
+// catches inf, i.e. the very first tile) the tile is redone with its exact max and the
+// accumulators are rescaled.  Row sums come from the bf16-rounded P, so numerator and
+// denominator see the same values.
+// ---------------------------------------------------------------------------------------------
+constexpr int kPPWaves = 8;
+constexpr int kPPBM = 256;
+constexpr int kKSlots = 2, kVSlots = 4;
+constexpr float kOptimisticLimit = 32768.0f;  // 2^15 per lane and tile (32 values)
+
+struct SmemPP {
+    union {
+        struct {
+            __bf16 k[kKSlots][kBN * kKStr];
+            __bf16 v[kVSlots][kBN * kVStr];
+        } t;
+        float merge[4 * 64 * 36];  // one query block of group B: [wave][9 vec4][lane][4]
+    };
+};
+
+// The loop body of both groups is straight-line code: every stage runs in every interval.  The
+// pipeline's fill and drain intervals and the tiles a wavefront cannot see are handled by data,
+// not by branches: P starts as zero, V slots start as zero, and a tile that must not contribute
+// is given a key offset beyond every row's bound so that the mask zeroes its P.  This keeps the
+// lifetimes of S, P and the operand fragments short and evident to the register allocator.
+__global__ void __launch_bounds__(kPPWaves * 64, 2)
+attn_fwd_bf16_d64_pp(FwdParams p) {
+    __shared__ SmemPP sm;
+    const WorkItem wi = decode_work(p);
+    if (!wi.valid) return;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int grp = wave >> 2, wq = wave & 3;
+    const int n = lane & 31, h = lane >> 5;
+    const int r0 = wi.q_tile * kPPBM;
+    const int r_last = min(r0 + kPPBM, p.Sq) - 1;
+    const int kmax_wg = kmax_of_row(r_last, p.T, p.P);
+    const int n_tiles = (kmax_wg + kBN - 1) / kBN;
+    const int tiles_per_split = (n_tiles + p.n_splits - 1) / p.n_splits;
+    const int t_begin = wi.split * tiles_per_split;
+    const int n_local = max(0, min(t_begin + tiles_per_split, n_tiles) - t_begin);
+
+    const __bf16* qg = (const __bf16*)p.q + (int64_t)wi.bh * p.Sq * kD;
+    const __bf16* kg = (const __bf16*)p.k + (int64_t)wi.bh * p.Scap * kD;
+    const __bf16* vg = (const __bf16*)p.v + (int64_t)wi.bh * p.Scap * kD;
+
+    const int rw0 = r0 + wq * 64;
+    int row[2], kmax_lane[2];
+    bf16x8 qf[2][4];
+#pragma unroll
+    for (int qt = 0; qt < 2; ++qt) {
+        row[qt] = rw0 + 32 * qt + n;
+        const int rc = min(row[qt], p.Sq - 1);  // ragged tail: compute a duplicate, never store it
+        kmax_lane[qt] = kmax_of_row(rc, p.T, p.P);
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) qf[qt][ks] = *(const bf16x8*)(qg + (int64_t)rc * kD + 16 * ks + 8 * h);
+    }
+    const int kmin_wave = kmax_of_row(min(rw0, p.Sq - 1), p.T, p.P);
+    const bool wave_active = rw0 < p.Sq;
+
+    f32x16 o_acc[2][2], s_acc[2][2];
+    bf16x8 pf[2][2][2];  // [kb][g][qt]
+    bf16x8 vf[2][2][2];  // [kb][g][dt]
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) { o_acc[a][b][r] = 0.f; s_acc[a][b][r] = 0.f; }
+#pragma unroll
+            for (int e = 0; e < 2; ++e)
+#pragma unroll
+                for (int x = 0; x < 8; ++x) { pf[a][b][e][x] = (__bf16)0.0f; vf[a][b][e][x] = (__bf16)0.0f; }
+        }
+    float m_used[2] = {kNegBig, kNegBig};
+    float l_sum[2] = {0.f, 0.f};
+    const float c = p.scale_log2e;
+
+    // V slots start as zeros: the fill intervals multiply them by P = 0 and must not meet NaN bits.
+    {
+        u32x4* vz = (u32x4*)&sm.t.v[0][0];
+        const u32x4 z = {0u, 0u, 0u, 0u};
+        for (int i = tid; i < kVSlots * kBN * kVStr / 8; i += kPPWaves * 64) vz[i] = z;
+    }
+
+    u32x4 kreg, vreg;
+    auto load_tile = [&](int i) {  // rows past the end are clamped: they are masked anyway
+        const int kr = min((t_begin + i) * kBN + (tid >> 3), p.Sk - 1);
+        const int64_t off = (int64_t)kr * kD + (tid & 7) * 8;
+        kreg = *(const u32x4*)(kg + off);
+        vreg = *(const u32x4*)(vg + off);
+    };
+    auto store_tile = [&](int i) {
+        *(u32x4*)(&sm.t.k[i & (kKSlots - 1)][(tid >> 3) * kKStr + (tid & 7) * 8]) = kreg;
+        *(u32x4*)(&sm.t.v[i & (kVSlots - 1)][(tid >> 3) * kVStr + (tid & 7) * 8]) = vreg;
+    };
+    const int k_off = n * kKStr + 8 * h;
+    const int s16 = lane & 15, dblk = (lane >> 4) & 1;
+    const int v_off = (4 * h + (s16 >> 2)) * kVStr + 16 * dblk + 4 * (s16 & 3);
+
+    // Requested at the end of the softmax stage, so the LDS latency hides behind the barrier.
+    auto read_v_frags = [&](int i) {
+        const __bf16* vs_ = sm.t.v[i & (kVSlots - 1)];
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int g = 0; g < 2; ++g)
+#pragma unroll
+                for (int dt = 0; dt < 2; ++dt) {
+                    const __bf16* vp = vs_ + v_off + (32 * kb + 16 * g) * kVStr + 32 * dt;
+                    const s16x4 lo = lds_read_tr(vp);
+                    const s16x4 hi = lds_read_tr(vp + 8 * kVStr);
+                    typedef __attribute__((ext_vector_type(8))) short s16x8;
+                    const s16x8 av = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                    vf[kb][g][dt] = __builtin_bit_cast(bf16x8, av);
+                }
+    };
+    auto pv_half = [&](int kb) {
+#pragma unroll
+        for (int g = 0; g < 2; ++g)
+#pragma unroll
+            for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+                for (int qt = 0; qt < 2; ++qt)
+                    o_acc[dt][qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[kb][g][dt], pf[kb][g][qt], o_acc[dt][qt], 0, 0, 0);
+    };
+    // Matrix-core stage: O^T += V^T . P^T of the group's previous tile, then S^T = K . Q^T of its
+    // next tile i_qk.  The K fragments are requested while the first product is still issuing.
+    auto stage_mfma = [&](int i_qk) {
+        bf16x8 kf[2][4];
+        // The matrix stage outranks the other group's softmax in instruction arbitration: its MFMAs then
+        // issue the moment the pipe frees up and the softmax's VALU work fills the cycles in between.
+        __builtin_amdgcn_s_setprio(3);
+        pv_half(0);
+        __builtin_amdgcn_sched_barrier(0);
+        const __bf16* ks_ = sm.t.k[i_qk & (kKSlots - 1)];
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) kf[kb][ks] = lds_read_b128(ks_ + k_off + 32 * kb * kKStr + 16 * ks);
+        __builtin_amdgcn_sched_barrier(0);
+        pv_half(1);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) {
+#pragma unroll
+            for (int qt = 0; qt < 2; ++qt)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) s_acc[kb][qt][r] = 0.f;
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+                for (int qt = 0; qt < 2; ++qt)
+                    s_acc[kb][qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kb][ks], qf[qt][ks], s_acc[kb][qt], 0, 0, 0);
+        }
+        __builtin_amdgcn_s_setprio(0);
+    };
+    auto form_p = [&]() {  // P = exp2(c*s - c*m_used) in bf16, row sums from the rounded values
+        const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+#pragma unroll
+        for (int qt = 0; qt < 2; ++qt) {
+            const float mc = m_used[qt] * c;
+            float l = l_sum[qt];
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int g = 0; g < 2; ++g)
+#pragma unroll
+                    for (int jj = 0; jj < 4; ++jj) {
+                        const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s_acc[kb][qt][8 * g + 2 * jj], c, -mc));
+                        const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s_acc[kb][qt][8 * g + 2 * jj + 1], c, -mc));
+                        const f32x2 pp = {p0, p1};
+                        const bf16x2 pb = __builtin_convertvector(pp, bf16x2);
+                        l = __builtin_amdgcn_fdot2_f32_bf16(pb, ones, l, false);
+                        pf[kb][g][qt][2 * jj] = pb[0];
+                        pf[kb][g][qt][2 * jj + 1] = pb[1];
+                    }
+            l_sum[qt] = l;
+        }
+    };
+#ifdef NFD_STAGE_TIMING
+    unsigned long long tsum[8] = {0, 0, 0, 0, 0, 0, 0, 0}, tc0, tc1;
+#define NFD_TOCK2(i) { __builtin_amdgcn_s_waitcnt(0xc07f); tc1 = __builtin_readcyclecounter(); tsum[i] += tc1 - tc0; tc0 = tc1; }
+#else
+#define NFD_TOCK2(i)
+#endif
+    // Softmax stage of local tile i (S in s_acc -> P in pf); a tile index outside the split's range
+    // is given an offset beyond every bound, which masks it completely.
+    auto stage_softmax = [&](int i) {
+        const int j0 = (i >= 0 && i < n_local) ? (t_begin + i) * kBN : 0x3fffff00;
+        if (__builtin_amdgcn_readfirstlane(j0 + kBN > kmin_wave)) {  // tile crosses some row's bound
+            asm volatile("" ::: "memory");  // keep this rare block a branch; do not if-convert it into every tile
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int qt = 0; qt < 2; ++qt)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int key = j0 + 32 * kb + 8 * (r >> 2) + 4 * h + (r & 3);
+                        if (key >= kmax_lane[qt]) s_acc[kb][qt][r] = -INFINITY;
+                    }
+        }
+        const float l_old0 = l_sum[0], l_old1 = l_sum[1];
+        NFD_TOCK2(5)
+        form_p();
+        NFD_TOCK2(6)
+        const bool bad = !(l_sum[0] - l_old0 < kOptimisticLimit) | !(l_sum[1] - l_old1 < kOptimisticLimit);
+        if (__builtin_amdgcn_ballot_w64(bad) != 0) {  // exact path: this tile's max, rescale, redo
+#ifdef NFD_STAGE_TIMING
+            tsum[4] += 1;
+#endif
+            l_sum[0] = l_old0;
+            l_sum[1] = l_old1;
+#pragma unroll
+            for (int qt = 0; qt < 2; ++qt) {
+                float a = fmaxf(s_acc[0][qt][0], s_acc[1][qt][0]);
+#pragma unroll
+                for (int r = 1; r < 16; ++r) a = fmaxf(fmaxf(a, s_acc[0][qt][r]), s_acc[1][qt][r]);
+                a = fmaxf(a, __shfl_xor(a, 32));
+                const float m_new = fmaxf(a, m_used[qt]);
+                const float alpha = __builtin_amdgcn_exp2f((m_used[qt] - m_new) * c);
+                m_used[qt] = m_new;
+                l_sum[qt] *= alpha;
+#pragma unroll
+                for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) o_acc[dt][qt][r] *= alpha;
+            }
+            form_p();
+        }
+    };
+
+    load_tile(0);
+    store_tile(0);
+    wait_vmem_all();
+    __syncthreads();
+
+    // Interval nn: group (nn & 1) runs P.V of tile nn-2 and K.Q^T of tile nn; the other group runs
+    // the softmax of tile nn-1 and fetches that tile's V fragments.  Everybody stages tile nn+1 and
+    // meets at a barrier.  Tile i belongs to group (i & 1).  K(i) is read in interval i and its slot
+    // (2 slots) rewritten in interval i+1; V(i) is read at the end of interval i+1 and its slot
+    // (4 slots) rewritten in interval i+3.
+    const int n_iter = n_local > 0 ? (n_local + 3) / 2 : 0;
+#ifdef NFD_STAGE_TIMING
+#define NFD_TOCK(i) { __builtin_amdgcn_s_waitcnt(0xc07f); tc1 = __builtin_readcyclecounter(); tsum[i] += tc1 - tc0; tc0 = tc1; }
+    tc0 = __builtin_readcyclecounter();
+#else
+#define NFD_TOCK(i)
+#endif
+    if (grp == 0) {
+        for (int it = 0; it < n_iter; ++it) {
+            const int nn = 2 * it;
+            load_tile(nn + 1);
+            stage_mfma(nn);
+            NFD_TOCK(0)
+            store_tile(nn + 1);
+            __syncthreads();
+            NFD_TOCK(1)
+            load_tile(nn + 2);
+            stage_softmax(nn);
+            read_v_frags(nn);
+            NFD_TOCK(2)
+            store_tile(nn + 2);
+            __syncthreads();
+            NFD_TOCK(3)
+        }
+    } else {
+        for (int it = 0; it < n_iter; ++it) {
+            const int nn = 2 * it;
+            load_tile(nn + 1);
+            stage_softmax(nn - 1);
+            read_v_frags(nn - 1);
+            NFD_TOCK(2)
+            store_tile(nn + 1);
+            __syncthreads();
+            NFD_TOCK(3)
+            load_tile(nn + 2);
+            stage_mfma(nn + 1);
+            NFD_TOCK(0)
+            store_tile(nn + 2);
+            __syncthreads();
+            NFD_TOCK(1)
+        }
+    }
+#ifdef NFD_STAGE_TIMING
+    if (p.timing && lane == 0) {
+        unsigned long long* o = p.timing + ((size_t)blockIdx.x * kPPWaves + wave) * 8;
+        for (int i = 0; i < 5; ++i) o[i] = tsum[i];
+        o[5] = (unsigned long long)(2 * n_iter);
+        o[6] = tsum[5];
+        o[7] = tsum[6];
+    }
+#endif
+    __syncthreads();
+
+    // ---- merge group B into group A (one 32-query block at a time through LDS), then store --------
+#pragma unroll
+    for (int qt = 0; qt < 2; ++qt) {
+        const float l_row = l_sum[qt] + __shfl_xor(l_sum[qt], 32);
+        float* mb = sm.merge + wq * (64 * 36);
+        if (grp == 1) {
+#pragma unroll
+            for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+                for (int rb = 0; rb < 4; ++rb) {
+                    const f32x4 x = {o_acc[dt][qt][4 * rb], o_acc[dt][qt][4 * rb + 1], o_acc[dt][qt][4 * rb + 2],
+                                     o_acc[dt][qt][4 * rb + 3]};
+                    *(f32x4*)(mb + ((dt * 4 + rb) * 64 + lane) * 4) = x;
+                }
+            const f32x4 ml = {m_used[qt], l_row, 0.f, 0.f};
+            *(f32x4*)(mb + (8 * 64 + lane) * 4) = ml;
+        }
+        __syncthreads();
+        if (grp == 0 && wave_active) {
+            const f32x4 ml = *(const f32x4*)(mb + (8 * 64 + lane) * 4);
+            const float m_all = fmaxf(m_used[qt], ml[0]);
+            const float wa = __builtin_amdgcn_exp2f((m_used[qt] - m_all) * c);
+            const float wb = __builtin_amdgcn_exp2f((ml[0] - m_all) * c);
+            const float l_all = l_row * wa + ml[1] * wb;
+            const bool store_row = row[qt] < p.Sq;
+            float scale_out = 1.0f;
+            if (p.n_splits == 1) scale_out = 1.0f / l_all;
+            const float fa = wa * scale_out, fb = wb * scale_out;
+            __bf16* og = (__bf16*)p.out + ((int64_t)wi.bh * p.Sq + row[qt]) * kD;
+            const int64_t prow = ((int64_t)wi.bh * p.n_splits + wi.split) * p.Sq + row[qt];
+#pragma unroll
+            for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+                for (int rb = 0; rb < 4; ++rb) {
+                    const f32x4 ob = *(const f32x4*)(mb + ((dt * 4 + rb) * 64 + lane) * 4);
+                    const f32x4 x = {o_acc[dt][qt][4 * rb] * fa + ob[0] * fb, o_acc[dt][qt][4 * rb + 1] * fa + ob[1] * fb,
+                                     o_acc[dt][qt][4 * rb + 2] * fa + ob[2] * fb, o_acc[dt][qt][4 * rb + 3] * fa + ob[3] * fb};
+                    if (store_row) {
+                        if (p.n_splits == 1) {
+                            const bf16x4 y = __builtin_convertvector(x, bf16x4);
+                            *(bf16x4*)(og + 32 * dt + 8 * rb + 4 * h) = y;
+                        } else {
+                            *(f32x4*)(p.part_o + prow * kD + 32 * dt + 8 * rb + 4 * h) = x;
+                        }
+                    }
+                }
+            if (p.n_splits > 1 && store_row && h == 0) {
+                const f32x2 o2 = {m_all * c, l_all};
+                *(f32x2*)(p.part_ml + prow * 2) = o2;
+            }
+        }
+        __syncthreads();
     }
 }
 

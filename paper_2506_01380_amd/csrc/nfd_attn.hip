@@ -191,11 +191,22 @@ int nfd_block_causal_attn_fwd(nfd_attn_t* h, const void* q, const void* k, const
         p.part_o = (float*)h->workspace;
         p.part_ml = p.part_o + (size_t)p.BH * pl.n_splits * p.Sq * nfd::mfma::kD;
     }
+#ifdef NFD_STAGE_TIMING
+    {
+        const char* e = getenv("NFD_TIMING_BUF");
+        p.timing = e ? (unsigned long long*)strtoull(e, nullptr, 0) : nullptr;
+    }
+#endif
     hipStream_t st = (hipStream_t)stream;
 
     if (pl.kernel == 1) {
-        hipLaunchKernelGGL(nfd::mfma::attn_fwd_bf16_d64<kMfmaWaves>, dim3(pl.n_workgroups), dim3(kMfmaWaves * 64), 0,
-                           st, p);
+        static const int variant = [] { const char* e = getenv("NFD_VARIANT"); return e ? atoi(e) : 1; }();
+        if (variant == 1)
+            hipLaunchKernelGGL(nfd::mfma::attn_fwd_bf16_d64<kMfmaWaves>, dim3(pl.n_workgroups), dim3(kMfmaWaves * 64), 0,
+                               st, p);
+        else
+            hipLaunchKernelGGL(nfd::mfma::attn_fwd_bf16_d64_pp, dim3(pl.n_workgroups), dim3(nfd::mfma::kPPWaves * 64), 0,
+                               st, p);
         if (pl.n_splits > 1) {
             const int64_t total = (int64_t)p.BH * p.Sq * (nfd::mfma::kD / 4);
             hipLaunchKernelGGL(nfd::mfma::attn_combine_d64, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, p);

@@ -39,6 +39,9 @@ struct FwdParams {
     int n_q_tiles;      // query tiles per head
     int n_splits;       // key splits per query tile
     float scale_log2e;  // softmax scale * log2(e)
+#ifdef NFD_STAGE_TIMING
+    unsigned long long* timing;  // development builds only: per-wavefront stage cycle sums
+#endif
 };
 
 __device__ __forceinline__ int kmax_of_row(int row, int T, int P) { return (P + row / T + 1) * T; }
