@@ -43,7 +43,7 @@ __device__ __forceinline__ s16x4 lds_read_tr(const __bf16* p) {
 __device__ __forceinline__ void wait_vmem_all() { __builtin_amdgcn_s_waitcnt(0x0F70); }
 
 template <int NW>
-struct Smem {
+struct __attribute__((aligned(16))) Smem {
     __bf16 k[2][kBN * kKStr];
     __bf16 v[2][kBN * kVStr];
 };
@@ -254,13 +254,13 @@ attn_fwd_bf16_d64(FwdParams p) {
                         for (int r = 0; r < 16; ++r) o_acc[dt][qt][r] *= alpha;
                 }
             }
-            // ---- P = exp2(c*s - c*m), bf16; row sums from the rounded values ------------------------
+            // ---- P = exp2(c*s - c*m), bf16; row sums in fp32 (plain adds: the packed dot
+    // instruction shares the matrix pipe and would stall the other wavefront's MFMAs) ------------------------
             bf16x8 pf[2][2][2];  // [kb][g][qt]
-            const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
 #pragma unroll
             for (int qt = 0; qt < 2; ++qt) {
                 const float mc = m_used[qt] * c;
-                float l = l_sum[qt];
+                float l = l_sum[qt], l2 = 0.f;
 #pragma unroll
                 for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
@@ -271,12 +271,13 @@ attn_fwd_bf16_d64(FwdParams p) {
                             const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s_acc[kb][qt][8 * g + 2 * jj + 1], c, -mc));
                             const f32x2 pp = {p0, p1};
                             const bf16x2 pb = __builtin_convertvector(pp, bf16x2);
-                            l = __builtin_amdgcn_fdot2_f32_bf16(pb, ones, l, false);
+                            l += p0;
+                            l2 += p1;
                             pf[kb][g][qt][2 * jj] = pb[0];
                             pf[kb][g][qt][2 * jj + 1] = pb[1];
                         }
                     }
-                l_sum[qt] = l;
+                l_sum[qt] = l + l2;
             }
             NFD_TICK(2)
             // ---- O^T += V^T . P^T -----------------------------------------------------------------
@@ -362,7 +363,7 @@ constexpr int kPPBM = 256;
 constexpr int kKSlots = 2, kVSlots = 4;
 constexpr float kOptimisticLimit = 32768.0f;  // 2^15 per lane and tile (32 values)
 
-struct SmemPP {
+struct __attribute__((aligned(16))) SmemPP {
     union {
         struct {
             __bf16 k[kKSlots][kBN * kKStr];
@@ -377,6 +378,9 @@ struct SmemPP {
 // not by branches: P starts as zero, V slots start as zero, and a tile that must not contribute
 // is given a key offset beyond every row's bound so that the mask zeroes its P.  This keeps the
 // lifetimes of S, P and the operand fragments short and evident to the register allocator.
+// DBG is 0 in the product; development builds instantiate variants that leave out one piece of work
+// (results are then wrong) to see what each piece costs in situ.
+template <int DBG>
 __global__ void __launch_bounds__(kPPWaves * 64, 2)
 attn_fwd_bf16_d64_pp(FwdParams p) {
     __shared__ SmemPP sm;
@@ -442,10 +446,12 @@ attn_fwd_bf16_d64_pp(FwdParams p) {
     auto load_tile = [&](int i) {  // rows past the end are clamped: they are masked anyway
         const int kr = min((t_begin + i) * kBN + (tid >> 3), p.Sk - 1);
         const int64_t off = (int64_t)kr * kD + (tid & 7) * 8;
+        if (DBG & 1) return;
         kreg = *(const u32x4*)(kg + off);
         vreg = *(const u32x4*)(vg + off);
     };
     auto store_tile = [&](int i) {
+        if (DBG & 2) return;
         *(u32x4*)(&sm.t.k[i & (kKSlots - 1)][(tid >> 3) * kKStr + (tid & 7) * 8]) = kreg;
         *(u32x4*)(&sm.t.v[i & (kVSlots - 1)][(tid >> 3) * kVStr + (tid & 7) * 8]) = vreg;
     };
@@ -455,6 +461,7 @@ attn_fwd_bf16_d64_pp(FwdParams p) {
 
     // Requested at the end of the softmax stage, so the LDS latency hides behind the barrier.
     auto read_v_frags = [&](int i) {
+        if (DBG & 4) return;
         const __bf16* vs_ = sm.t.v[i & (kVSlots - 1)];
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
@@ -471,6 +478,7 @@ attn_fwd_bf16_d64_pp(FwdParams p) {
                 }
     };
     auto pv_half = [&](int kb) {
+        if (DBG & 32) return;
 #pragma unroll
         for (int g = 0; g < 2; ++g)
 #pragma unroll
@@ -492,10 +500,14 @@ attn_fwd_bf16_d64_pp(FwdParams p) {
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-            for (int ks = 0; ks < 4; ++ks) kf[kb][ks] = lds_read_b128(ks_ + k_off + 32 * kb * kKStr + 16 * ks);
+            for (int ks = 0; ks < 4; ++ks) {
+                if (DBG & 8) kf[kb][ks] = vf[kb][ks >> 1][ks & 1];
+                else kf[kb][ks] = lds_read_b128(ks_ + k_off + 32 * kb * kKStr + 16 * ks);
+            }
         __builtin_amdgcn_sched_barrier(0);
         pv_half(1);
         __builtin_amdgcn_sched_barrier(0);
+        if (!(DBG & 32))
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb) {
 #pragma unroll
@@ -510,12 +522,12 @@ attn_fwd_bf16_d64_pp(FwdParams p) {
         }
         __builtin_amdgcn_s_setprio(0);
     };
-    auto form_p = [&]() {  // P = exp2(c*s - c*m_used) in bf16, row sums from the rounded values
-        const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+    auto form_p = [&]() {  // P = exp2(c*s - c*m_used) in bf16, row sums in fp32 (plain adds: the packed dot
+    // instruction shares the matrix pipe and would stall the other wavefront's MFMAs)
 #pragma unroll
         for (int qt = 0; qt < 2; ++qt) {
             const float mc = m_used[qt] * c;
-            float l = l_sum[qt];
+            float l = l_sum[qt], l2 = 0.f;
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
@@ -526,11 +538,12 @@ attn_fwd_bf16_d64_pp(FwdParams p) {
                         const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s_acc[kb][qt][8 * g + 2 * jj + 1], c, -mc));
                         const f32x2 pp = {p0, p1};
                         const bf16x2 pb = __builtin_convertvector(pp, bf16x2);
-                        l = __builtin_amdgcn_fdot2_f32_bf16(pb, ones, l, false);
+                        l += p0;
+                        l2 += p1;
                         pf[kb][g][qt][2 * jj] = pb[0];
                         pf[kb][g][qt][2 * jj + 1] = pb[1];
                     }
-            l_sum[qt] = l;
+            l_sum[qt] = l + l2;
         }
     };
 #ifdef NFD_STAGE_TIMING
@@ -556,9 +569,8 @@ attn_fwd_bf16_d64_pp(FwdParams p) {
                     }
         }
         const float l_old0 = l_sum[0], l_old1 = l_sum[1];
-        NFD_TOCK2(5)
+        if (DBG & 16) return;
         form_p();
-        NFD_TOCK2(6)
         const bool bad = !(l_sum[0] - l_old0 < kOptimisticLimit) | !(l_sum[1] - l_old1 < kOptimisticLimit);
         if (__builtin_amdgcn_ballot_w64(bad) != 0) {  // exact path: this tile's max, rescale, redo
 #ifdef NFD_STAGE_TIMING

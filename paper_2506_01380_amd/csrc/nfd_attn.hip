@@ -205,8 +205,20 @@ int nfd_block_causal_attn_fwd(nfd_attn_t* h, const void* q, const void* k, const
             hipLaunchKernelGGL(nfd::mfma::attn_fwd_bf16_d64<kMfmaWaves>, dim3(pl.n_workgroups), dim3(kMfmaWaves * 64), 0,
                                st, p);
         else
-            hipLaunchKernelGGL(nfd::mfma::attn_fwd_bf16_d64_pp, dim3(pl.n_workgroups), dim3(nfd::mfma::kPPWaves * 64), 0,
+        {
+#ifdef NFD_DEBUG_VARIANTS
+            static const int dbg = [] { const char* e = getenv("NFD_DBG"); return e ? atoi(e) : 0; }();
+#define NFD_DBG_CASE(D) case D: hipLaunchKernelGGL(nfd::mfma::attn_fwd_bf16_d64_pp<D>, dim3(pl.n_workgroups), dim3(nfd::mfma::kPPWaves * 64), 0, st, p); break;
+            switch (dbg) {
+                NFD_DBG_CASE(1) NFD_DBG_CASE(3) NFD_DBG_CASE(4) NFD_DBG_CASE(8) NFD_DBG_CASE(12) NFD_DBG_CASE(15) NFD_DBG_CASE(16) NFD_DBG_CASE(32) NFD_DBG_CASE(47) NFD_DBG_CASE(31)
+                default:
+#endif
+            hipLaunchKernelGGL(nfd::mfma::attn_fwd_bf16_d64_pp<0>, dim3(pl.n_workgroups), dim3(nfd::mfma::kPPWaves * 64), 0,
                                st, p);
+#ifdef NFD_DEBUG_VARIANTS
+            }
+#endif
+        }
         if (pl.n_splits > 1) {
             const int64_t total = (int64_t)p.BH * p.Sq * (nfd::mfma::kD / 4);
             hipLaunchKernelGGL(nfd::mfma::attn_combine_d64, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, p);
