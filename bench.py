@@ -29,6 +29,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of the oracle sample")
     ap.add_argument("--all", action="store_true", help="also time the other workloads (reported on stderr)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a 1 GiB device copy a few times (a kernel of known HBM bytes, for scaling profiler counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
@@ -83,6 +85,18 @@ def main():
     main_res = time_workload(args.workload, args.steps, args.warmup)
     cfg = main_res["cfg"]
 
+    if args.calibrate_copy:
+        # kvcache_append is a plain copy: here exactly 1 GiB read and 1 GiB written per launch (K and V, 512 MiB each)
+        cb, ch, cf, ct, cd = 4, 16, 64, 1024, 64
+        kc = torch.zeros((cb, ch, cf * ct, cd), dtype=torch.bfloat16, device="cuda")
+        vc = torch.zeros_like(kc)
+        kn = torch.ones_like(kc)
+        vn = torch.ones_like(kc)
+        for _ in range(4):
+            nb.nfd_kvcache_append(attn.h, kc, vc, kn, vn, cb, ch, cf, ct, cd, 0, cf)
+        torch.cuda.synchronize()
+        del kc, vc, kn, vn
+
     others = []
     if args.all:
         for name in wl.CONFIGS:
@@ -101,22 +115,36 @@ def main():
         _, q, k, v = wl.make_config(args.workload)
         cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
 
-        def run_rows(per_frame):
-            rows = wl.sample_rows(T, qf, per_frame, cfg["seed"])
+        q64, k64, v64 = (np.asarray(x, dtype=np.float64) for x in (q, k, v))  # exact widening, outside the timed part
+        P = kvf - qf
+
+        def run_rows(rows):
             t0 = time.perf_counter()
-            orc.block_causal_attn(q, k, v, T, kv_frames=kvf, q_frames=qf, rows=rows)
+            orc.block_causal_attn(q64, k64, v64, T, kv_frames=kvf, q_frames=qf, rows=rows)
             dt = time.perf_counter() - t0
-            P = kvf - qf
-            pairs = sum((P + r // T + 1) * T for r in rows) * B * H
-            return dt, 4 * D * pairs, len(rows)
+            idx = np.arange(qf * T) if rows is None else rows
+            pairs = int(sum((P + int(r) // T + 1) * T for r in idx)) * B * H
+            return dt, 4 * D * pairs, len(idx)
 
-        dt, fl, n = run_rows(0)  # two rows per frame: calibration (includes fp64 widening of the inputs)
-        per_frame = int(max(1, min(T - 2, (args.cpu_seconds / max(dt, 1e-3)) * 2 - 2)))
-        dt, fl, n = run_rows(per_frame)
-        cpu = dict(value=fl / dt * 1e-12, unit="TFLOP/s", cores=cores, kind="oracle",
-                   sample="%d of %d query rows per head (first+last+%d random rows of each frame), all %d heads, %.1f s"
-                          % (n, qf * T, per_frame, B * H, dt))
+        # calibrate on two rows per frame, then size the sample for about --cpu-seconds of oracle time
+        dt0, fl0, n0 = run_rows(wl.sample_rows(T, qf, 0, cfg["seed"]))
+        rows_fit = int(n0 * args.cpu_seconds / max(dt0, 1e-4))
+        if rows_fit >= qf * T:
+            dt, fl, n = run_rows(None)
+            what = "all %d query rows of all %d heads (the whole workload)" % (qf * T, B * H)
+        else:
+            per_frame = max(1, rows_fit // qf - 2)
+            dt, fl, n = run_rows(wl.sample_rows(T, qf, per_frame, cfg["seed"]))
+            what = "%d of %d query rows per head (first, last and %d random rows of each frame), all %d heads" % (
+                n, qf * T, per_frame, B * H)
+        cpu = dict(value=round(fl / dt * 1e-12, 5), unit="TFLOP/s", cores=cores, kind="oracle",
+                   sample="%s, %.1f s of oracle time" % (what, dt))
 
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if os.path.exists(tpath):
+        with open(tpath) as f:
+            traffic = json.load(f).get(args.workload, {}).get("bytes_per_launch")
     frac = main_res["tflops"] / PEAK_BF16_TFLOPS
     line = {
         "metric": "block-causal attn TFLOP/s (unmasked) + % bf16 MFMA peak; attn-layer frames/s",
@@ -128,7 +156,7 @@ def main():
                    "pct_bf16_mfma_peak": round(100 * frac, 2),
                    "attn_layer_frames_per_s": round(main_res["frames_per_s"], 1), "plan": main_res["plan"]},
         "roofline": {"bound": "mfma", "achieved": round(main_res["tflops"], 2), "peak": PEAK_BF16_TFLOPS,
-                     "unit": "TFLOP/s", "frac": round(frac, 4), "traffic": None,
+                     "unit": "TFLOP/s", "frac": round(frac, 4), "traffic": traffic,
                      "kernel": "attn_fwd_bf16_d64"},
         "cpu_baseline": cpu,
     }
