@@ -14,6 +14,7 @@
 
 #include "kernels_generic.hpp"
 #include "kernels_mfma.hpp"
+#include "kernels_mfma_dma.hpp"
 
 struct nfd_attn {
     nfd_dtype_t dtype;
@@ -204,6 +205,20 @@ int nfd_block_causal_attn_fwd(nfd_attn_t* h, const void* q, const void* k, const
         if (variant == 1)
             hipLaunchKernelGGL(nfd::mfma::attn_fwd_bf16_d64<kMfmaWaves>, dim3(pl.n_workgroups), dim3(kMfmaWaves * 64), 0,
                                st, p);
+        else if (variant == 3) {
+#ifdef NFD_DEBUG_VARIANTS
+            static const int dbg3 = [] { const char* e = getenv("NFD_DBG"); return e ? atoi(e) : 0; }();
+#define NFD_DBG3_CASE(D) case D: hipLaunchKernelGGL(nfd::mfma::attn_fwd_bf16_d64_dma<D>, dim3(pl.n_workgroups), dim3(nfd::mfma::kPPWaves * 64), 0, st, p); break;
+            switch (dbg3) {
+                NFD_DBG3_CASE(1) NFD_DBG3_CASE(2) NFD_DBG3_CASE(4) NFD_DBG3_CASE(8) NFD_DBG3_CASE(16) NFD_DBG3_CASE(28) NFD_DBG3_CASE(29) NFD_DBG3_CASE(30) NFD_DBG3_CASE(3) NFD_DBG3_CASE(60) NFD_DBG3_CASE(92) NFD_DBG3_CASE(124) NFD_DBG3_CASE(61) NFD_DBG3_CASE(62)
+                default:
+#endif
+            hipLaunchKernelGGL(nfd::mfma::attn_fwd_bf16_d64_dma<0>, dim3(pl.n_workgroups), dim3(nfd::mfma::kPPWaves * 64), 0,
+                               st, p);
+#ifdef NFD_DEBUG_VARIANTS
+            }
+#endif
+        }
         else
         {
 #ifdef NFD_DEBUG_VARIANTS
