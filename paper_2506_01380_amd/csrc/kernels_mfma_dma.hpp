@@ -231,6 +231,14 @@ attn_fwd_bf16_d64_dma(FwdParams p) {
         const float l_old0 = l_sum[0], l_old1 = l_sum[1];
         if (DBG & 1) return;
         form_p();
+        // Pin the packed P before the test: otherwise the compiler, seeing P rebuilt on the rare path,
+        // postpones all conversions until after the branch and keeps the 64 exponentials alive across it.
+#pragma unroll
+        for (int a = 0; a < 2; ++a)
+#pragma unroll
+            for (int b = 0; b < 2; ++b)
+#pragma unroll
+                for (int e = 0; e < 2; ++e) asm volatile("" : "+v"(pf[a][b][e]));
         const bool bad = !(l_sum[0] - l_old0 < kOptimisticLimit) | !(l_sum[1] - l_old1 < kOptimisticLimit);
         if (__builtin_amdgcn_ballot_w64(bad) != 0) {  // exact path: this tile's max, rescale, redo
             l_sum[0] = l_old0;
@@ -270,7 +278,11 @@ attn_fwd_bf16_d64_dma(FwdParams p) {
     auto interval_end = [&]() {
         __builtin_amdgcn_sched_barrier(0);
         wait_older_tiles();
-        __syncthreads();
+        // A bare barrier, not __syncthreads(): the fence of the latter would also wait for the V^T
+        // fragment reads issued just before it, whose latency is meant to pass behind the barrier.
+        // Nothing else needs the fence: LDS is written only by the tile loads, which the explicit
+        // vmcnt wait above orders, and the slots being read are not rewritten for two more intervals.
+        __builtin_amdgcn_s_barrier();
         __builtin_amdgcn_sched_barrier(0);
     };
     const int n_iter = n_local > 0 ? (n_local + 3) / 2 : 0;

@@ -89,14 +89,24 @@ int nfd_attn_plan(nfd_dtype_t dtype, int B, int H, int F, int T, int D, int kv_f
             visited += nt;
             max_tiles = std::max(max_tiles, nt);
         }
-        // Key splits: only when the query tiles alone cannot fill the chip (cached forms).
+        // Key splits: only when the query tiles alone cannot fill the chip (cached forms).  The count
+        // minimises a small cost model in units of one key tile: workgroups run in rounds of 2 per CU,
+        // a workgroup that has its CU to itself runs about twice as fast, every workgroup pays a fixed
+        // prologue/epilogue, and the combine pass grows with the number of partials.
         const int64_t slots = (int64_t)num_cus * 2, base = BH * pl.n_q_tiles;
         int splits = 1;
         if (base < slots) {
-            splits = (int)((slots + base - 1) / base);
-            splits = (int)std::min<int64_t>(splits, std::max<int64_t>(1, max_tiles / 4));
             const size_t per_split = (size_t)(BH * Sq) * (nfd::mfma::kD + 2) * sizeof(float);
-            while (splits > 1 && per_split * splits > workspace_limit) --splits;
+            double best = 1e30;
+            for (int s = 1; s <= 64 && s <= std::max<int64_t>(1, max_tiles / 2); ++s) {
+                if (s > 1 && per_split * s > workspace_limit) break;
+                const int64_t wgs = base * s;
+                const int64_t rounds = (wgs + slots - 1) / slots;
+                const double len = (double)((max_tiles + s - 1) / s) + 3.0;
+                const double pace = (rounds == 1 && wgs <= num_cus) ? 0.55 : 1.0;
+                const double cost = rounds * len * pace + (s > 1 ? 2.0 + 0.25 * s : 0.0);
+                if (cost < best) { best = cost; splits = s; }
+            }
         }
         pl.n_splits = splits;
         pl.n_workgroups = (int)(8 * ((BH + 7) / 8) * pl.n_q_tiles * splits);
@@ -210,7 +220,7 @@ int nfd_block_causal_attn_fwd(nfd_attn_t* h, const void* q, const void* k, const
             static const int dbg3 = [] { const char* e = getenv("NFD_DBG"); return e ? atoi(e) : 0; }();
 #define NFD_DBG3_CASE(D) case D: hipLaunchKernelGGL(nfd::mfma::attn_fwd_bf16_d64_dma<D>, dim3(pl.n_workgroups), dim3(nfd::mfma::kPPWaves * 64), 0, st, p); break;
             switch (dbg3) {
-                NFD_DBG3_CASE(1) NFD_DBG3_CASE(2) NFD_DBG3_CASE(4) NFD_DBG3_CASE(8) NFD_DBG3_CASE(16) NFD_DBG3_CASE(28) NFD_DBG3_CASE(29) NFD_DBG3_CASE(30) NFD_DBG3_CASE(3) NFD_DBG3_CASE(60) NFD_DBG3_CASE(92) NFD_DBG3_CASE(124) NFD_DBG3_CASE(61) NFD_DBG3_CASE(62)
+                NFD_DBG3_CASE(1) NFD_DBG3_CASE(2) NFD_DBG3_CASE(4) NFD_DBG3_CASE(8) NFD_DBG3_CASE(16) NFD_DBG3_CASE(28) NFD_DBG3_CASE(29) NFD_DBG3_CASE(30) NFD_DBG3_CASE(3) NFD_DBG3_CASE(32) NFD_DBG3_CASE(60) NFD_DBG3_CASE(92) NFD_DBG3_CASE(124) NFD_DBG3_CASE(61) NFD_DBG3_CASE(62)
                 default:
 #endif
             hipLaunchKernelGGL(nfd::mfma::attn_fwd_bf16_d64_dma<0>, dim3(pl.n_workgroups), dim3(nfd::mfma::kPPWaves * 64), 0,
