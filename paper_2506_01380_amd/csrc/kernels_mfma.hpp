@@ -69,6 +69,47 @@ __device__ __forceinline__ WorkItem decode_work(const FwdParams& p) {
     return w;
 }
 
+// Final write of one wavefront's 64 query rows: normalised bf16 output when the keys were not
+// split, otherwise the unnormalised fp32 accumulator plus (reference max in log2 units, row sum).
+// Lane (n, h) holds, for query column n of block qt, output features 32*dt + 8*rb + 4*h + 0..3.
+__device__ __forceinline__ void store_rows(const FwdParams& p, const WorkItem& wi, const int (&row)[2], int h,
+                                           const f32x16 (&o_acc)[2][2], const float (&l_sum)[2],
+                                           const float (&m_used)[2], float c) {
+#pragma unroll
+    for (int qt = 0; qt < 2; ++qt) {
+        const float l_row = l_sum[qt] + __shfl_xor(l_sum[qt], 32);
+        if (row[qt] >= p.Sq) continue;
+        if (p.n_splits == 1) {
+            const float inv = 1.0f / l_row;
+            __bf16* og = (__bf16*)p.out + ((int64_t)wi.bh * p.Sq + row[qt]) * kD;
+#pragma unroll
+            for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+                for (int rb = 0; rb < 4; ++rb) {
+                    const f32x4 x = {o_acc[dt][qt][4 * rb] * inv, o_acc[dt][qt][4 * rb + 1] * inv,
+                                     o_acc[dt][qt][4 * rb + 2] * inv, o_acc[dt][qt][4 * rb + 3] * inv};
+                    const bf16x4 y = __builtin_convertvector(x, bf16x4);
+                    *(bf16x4*)(og + 32 * dt + 8 * rb + 4 * h) = y;
+                }
+        } else {
+            const int64_t prow = ((int64_t)wi.bh * p.n_splits + wi.split) * p.Sq + row[qt];
+            float* po = p.part_o + prow * kD;
+#pragma unroll
+            for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+                for (int rb = 0; rb < 4; ++rb) {
+                    const f32x4 x = {o_acc[dt][qt][4 * rb], o_acc[dt][qt][4 * rb + 1], o_acc[dt][qt][4 * rb + 2],
+                                     o_acc[dt][qt][4 * rb + 3]};
+                    *(f32x4*)(po + 32 * dt + 8 * rb + 4 * h) = x;
+                }
+            if (h == 0) {
+                const f32x2 ml = {m_used[qt] * c, l_row};
+                *(f32x2*)(p.part_ml + prow * 2) = ml;
+            }
+        }
+    }
+}
+
 template <int NW>
 __global__ void __launch_bounds__(NW * 64, 2)
 attn_fwd_bf16_d64(FwdParams p) {
@@ -308,39 +349,7 @@ attn_fwd_bf16_d64(FwdParams p) {
 
     // ---- epilogue -----------------------------------------------------------------------------
     if (!wave_active) return;
-#pragma unroll
-    for (int qt = 0; qt < 2; ++qt) {
-        const float l_row = l_sum[qt] + __shfl_xor(l_sum[qt], 32);
-        if (row[qt] >= p.Sq) continue;
-        if (p.n_splits == 1) {
-            const float inv = 1.0f / l_row;
-            __bf16* og = (__bf16*)p.out + ((int64_t)wi.bh * p.Sq + row[qt]) * kD;
-#pragma unroll
-            for (int dt = 0; dt < 2; ++dt)
-#pragma unroll
-                for (int rb = 0; rb < 4; ++rb) {
-                    const f32x4 x = {o_acc[dt][qt][4 * rb] * inv, o_acc[dt][qt][4 * rb + 1] * inv,
-                                     o_acc[dt][qt][4 * rb + 2] * inv, o_acc[dt][qt][4 * rb + 3] * inv};
-                    const bf16x4 y = __builtin_convertvector(x, bf16x4);
-                    *(bf16x4*)(og + 32 * dt + 8 * rb + 4 * h) = y;
-                }
-        } else {
-            const int64_t prow = ((int64_t)wi.bh * p.n_splits + wi.split) * p.Sq + row[qt];
-            float* po = p.part_o + prow * kD;
-#pragma unroll
-            for (int dt = 0; dt < 2; ++dt)
-#pragma unroll
-                for (int rb = 0; rb < 4; ++rb) {
-                    const f32x4 x = {o_acc[dt][qt][4 * rb], o_acc[dt][qt][4 * rb + 1], o_acc[dt][qt][4 * rb + 2],
-                                     o_acc[dt][qt][4 * rb + 3]};
-                    *(f32x4*)(po + 32 * dt + 8 * rb + 4 * h) = x;
-                }
-            if (h == 0) {
-                const f32x2 ml = {m_used[qt] * c, l_row};
-                *(f32x2*)(p.part_ml + prow * 2) = ml;
-            }
-        }
-    }
+    store_rows(p, wi, row, h, o_acc, l_sum, m_used, c);
 }
 
 // ---------------------------------------------------------------------------------------------

@@ -14,7 +14,7 @@
 
 #include "kernels_generic.hpp"
 #include "kernels_mfma.hpp"
-#include "kernels_mfma_dma.hpp"
+#include "kernels_mfma_direct.hpp"
 
 struct nfd_attn {
     nfd_dtype_t dtype;
@@ -215,6 +215,10 @@ int nfd_block_causal_attn_fwd(nfd_attn_t* h, const void* q, const void* k, const
         if (variant == 1)
             hipLaunchKernelGGL(nfd::mfma::attn_fwd_bf16_d64<kMfmaWaves>, dim3(pl.n_workgroups), dim3(kMfmaWaves * 64), 0,
                                st, p);
+        else if (variant == 4)
+            hipLaunchKernelGGL(nfd::mfma::attn_fwd_bf16_d64_direct<1>, dim3(pl.n_workgroups), dim3(256), 0, st, p);
+        else if (variant == 5)
+            hipLaunchKernelGGL(nfd::mfma::attn_fwd_bf16_d64_direct<0>, dim3(pl.n_workgroups), dim3(256), 0, st, p);
         else if (variant == 3) {
 #ifdef NFD_DEBUG_VARIANTS
             static const int dbg3 = [] { const char* e = getenv("NFD_DBG"); return e ? atoi(e) : 0; }();
