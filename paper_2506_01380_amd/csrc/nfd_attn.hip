@@ -14,7 +14,6 @@
 
 #include "kernels_generic.hpp"
 #include "kernels_mfma.hpp"
-#include "kernels_mfma_direct.hpp"
 
 struct nfd_attn {
     nfd_dtype_t dtype;
@@ -28,7 +27,6 @@ struct nfd_attn {
 namespace {
 
 constexpr size_t kDefaultWorkspace = (size_t)128 << 20;
-constexpr int kMfmaWaves = 4;
 
 int fail(nfd_attn_t* h, int code, const std::string& msg) {
     if (h) h->err = msg;
@@ -79,7 +77,7 @@ int nfd_attn_plan(nfd_dtype_t dtype, int B, int H, int F, int T, int D, int kv_f
     nfd_attn_plan_t pl{};
     if (dtype == NFD_BF16 && D == nfd::mfma::kD) {
         pl.kernel = 1;
-        pl.block_m = kMfmaWaves * 64;
+        pl.block_m = nfd::mfma::kBM;
         pl.block_n = nfd::mfma::kBN;
         pl.n_q_tiles = (int)((Sq + pl.block_m - 1) / pl.block_m);
         int64_t visited = 0, max_tiles = 0;
@@ -90,9 +88,11 @@ int nfd_attn_plan(nfd_dtype_t dtype, int B, int H, int F, int T, int D, int kv_f
             max_tiles = std::max(max_tiles, nt);
         }
         // Key splits: only when the query tiles alone cannot fill the chip (cached forms).  The count
-        // minimises a small cost model in units of one key tile: workgroups run in rounds of 2 per CU,
-        // a workgroup that has its CU to itself runs about twice as fast, every workgroup pays a fixed
-        // prologue/epilogue, and the combine pass grows with the number of partials.
+        // minimises a small cost model in units of the time one workgroup needs for one key tile when
+        // two workgroups share a CU: workgroups run in rounds of 2 per CU; a workgroup that has its CU
+        // to itself is about 1.2x faster (measured); every workgroup pays a fixed prologue/epilogue of
+        // about three tiles; the combine pass costs a launch plus the write and read of the partials,
+        // which grows with rows x splits (about one unit per 15000 row-partials at HBM speed).
         const int64_t slots = (int64_t)num_cus * 2, base = BH * pl.n_q_tiles;
         int splits = 1;
         if (base < slots) {
@@ -103,11 +103,19 @@ int nfd_attn_plan(nfd_dtype_t dtype, int B, int H, int F, int T, int D, int kv_f
                 const int64_t wgs = base * s;
                 const int64_t rounds = (wgs + slots - 1) / slots;
                 const double len = (double)((max_tiles + s - 1) / s) + 3.0;
-                const double pace = (rounds == 1 && wgs <= num_cus) ? 0.55 : 1.0;
-                const double cost = rounds * len * pace + (s > 1 ? 2.0 + 0.25 * s : 0.0);
+                const double pace = wgs <= num_cus ? 0.83 : 1.0;
+                const double combine = s > 1 ? 1.0 + (double)s * (double)(BH * Sq) / 15000.0 : 0.0;
+                const double cost = rounds * len * pace + combine;
                 if (cost < best) { best = cost; splits = s; }
             }
         }
+#ifdef NFD_TUNE_SPLITS  // development build: sweep the split count from the environment
+        if (const char* e = getenv("NFD_SPLITS")) {
+            const size_t per_split = (size_t)(BH * Sq) * (nfd::mfma::kD + 2) * sizeof(float);
+            splits = std::max(1, std::min(atoi(e), (int)std::max<int64_t>(1, max_tiles / 2)));
+            while (splits > 1 && per_split * splits > workspace_limit) --splits;  // never beyond the workspace
+        }
+#endif
         pl.n_splits = splits;
         pl.n_workgroups = (int)(8 * ((BH + 7) / 8) * pl.n_q_tiles * splits);
         pl.key_tiles_visited = visited * BH;
@@ -184,6 +192,9 @@ int nfd_block_causal_attn_fwd(nfd_attn_t* h, const void* q, const void* k, const
     nfd_attn_plan_t pl;
     const int rc = nfd_attn_plan(h->dtype, B, H, F, T, D, kv_frames, q_frames, h->num_cus, h->workspace_bytes, &pl);
     if (rc != NFD_OK) return fail(h, rc, "invalid shape arguments");
+    // The plan is made against this handle's workspace; a schedule that would write partials past it
+    // must never reach the device.
+    if (pl.workspace_bytes > h->workspace_bytes) return fail(h, NFD_ERR_ALLOC, "key-split partials exceed the workspace");
     if (!(scale > 0.f)) scale = 1.0f / std::sqrt((float)D);
 
     nfd::FwdParams p{};
@@ -211,43 +222,7 @@ int nfd_block_causal_attn_fwd(nfd_attn_t* h, const void* q, const void* k, const
     hipStream_t st = (hipStream_t)stream;
 
     if (pl.kernel == 1) {
-        static const int variant = [] { const char* e = getenv("NFD_VARIANT"); return e ? atoi(e) : 1; }();
-        if (variant == 1)
-            hipLaunchKernelGGL(nfd::mfma::attn_fwd_bf16_d64<kMfmaWaves>, dim3(pl.n_workgroups), dim3(kMfmaWaves * 64), 0,
-                               st, p);
-        else if (variant == 4)
-            hipLaunchKernelGGL(nfd::mfma::attn_fwd_bf16_d64_direct<1>, dim3(pl.n_workgroups), dim3(256), 0, st, p);
-        else if (variant == 5)
-            hipLaunchKernelGGL(nfd::mfma::attn_fwd_bf16_d64_direct<0>, dim3(pl.n_workgroups), dim3(256), 0, st, p);
-        else if (variant == 3) {
-#ifdef NFD_DEBUG_VARIANTS
-            static const int dbg3 = [] { const char* e = getenv("NFD_DBG"); return e ? atoi(e) : 0; }();
-#define NFD_DBG3_CASE(D) case D: hipLaunchKernelGGL(nfd::mfma::attn_fwd_bf16_d64_dma<D>, dim3(pl.n_workgroups), dim3(nfd::mfma::kPPWaves * 64), 0, st, p); break;
-            switch (dbg3) {
-                NFD_DBG3_CASE(1) NFD_DBG3_CASE(2) NFD_DBG3_CASE(4) NFD_DBG3_CASE(8) NFD_DBG3_CASE(16) NFD_DBG3_CASE(28) NFD_DBG3_CASE(29) NFD_DBG3_CASE(30) NFD_DBG3_CASE(3) NFD_DBG3_CASE(32) NFD_DBG3_CASE(60) NFD_DBG3_CASE(92) NFD_DBG3_CASE(124) NFD_DBG3_CASE(61) NFD_DBG3_CASE(62)
-                default:
-#endif
-            hipLaunchKernelGGL(nfd::mfma::attn_fwd_bf16_d64_dma<0>, dim3(pl.n_workgroups), dim3(nfd::mfma::kPPWaves * 64), 0,
-                               st, p);
-#ifdef NFD_DEBUG_VARIANTS
-            }
-#endif
-        }
-        else
-        {
-#ifdef NFD_DEBUG_VARIANTS
-            static const int dbg = [] { const char* e = getenv("NFD_DBG"); return e ? atoi(e) : 0; }();
-#define NFD_DBG_CASE(D) case D: hipLaunchKernelGGL(nfd::mfma::attn_fwd_bf16_d64_pp<D>, dim3(pl.n_workgroups), dim3(nfd::mfma::kPPWaves * 64), 0, st, p); break;
-            switch (dbg) {
-                NFD_DBG_CASE(1) NFD_DBG_CASE(3) NFD_DBG_CASE(4) NFD_DBG_CASE(8) NFD_DBG_CASE(12) NFD_DBG_CASE(15) NFD_DBG_CASE(16) NFD_DBG_CASE(32) NFD_DBG_CASE(47) NFD_DBG_CASE(31)
-                default:
-#endif
-            hipLaunchKernelGGL(nfd::mfma::attn_fwd_bf16_d64_pp<0>, dim3(pl.n_workgroups), dim3(nfd::mfma::kPPWaves * 64), 0,
-                               st, p);
-#ifdef NFD_DEBUG_VARIANTS
-            }
-#endif
-        }
+        hipLaunchKernelGGL(nfd::mfma::attn_fwd_bf16_d64, dim3(pl.n_workgroups), dim3(nfd::mfma::kWaves * 64), 0, st, p);
         if (pl.n_splits > 1) {
             const int64_t total = (int64_t)p.BH * p.Sq * (nfd::mfma::kD / 4);
             hipLaunchKernelGGL(nfd::mfma::attn_combine_d64, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, p);
