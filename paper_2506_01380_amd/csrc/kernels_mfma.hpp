@@ -73,7 +73,12 @@ struct __attribute__((aligned(16))) SmemRing {
 
 // Work decomposition of one launch.  Workgroup ids are dealt round-robin to the 8 XCDs;
 // heads are pinned to an XCD (bh % 8) so that all query tiles and key splits of a head
-// share one L2, and inside an XCD the heaviest query tiles (latest frames) come first.
+// share one L2.  Inside an XCD:
+//  * by default the heaviest query tiles (latest frames) come first, heads fastest, so the tail
+//    of the launch is made of the lightest tiles;
+//  * group_q_tiles (key-split launches whose K/V exceed the last-level cache): the query tiles of
+//    one (head, split) are consecutive instead, so they are resident together and their common
+//    K/V range is fetched from HBM once and found in L2 by the others.
 struct WorkItem {
     int bh, q_tile, split;
     bool valid;
@@ -84,11 +89,20 @@ __device__ __forceinline__ WorkItem decode_work(const FwdParams& p) {
     const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
     const int heads_here = p.BH / 8 + (xcd < (p.BH & 7) ? 1 : 0);
     w.valid = heads_here > 0 && j < heads_here * per_head;
-    const int item = heads_here > 0 ? j / heads_here : 0;
-    const int head_local = heads_here > 0 ? j % heads_here : 0;
+    const int hh = max(heads_here, 1);
+    int head_local;
+    if (!p.group_q_tiles) {
+        const int item = j / hh;
+        head_local = j % hh;
+        w.q_tile = p.n_q_tiles - 1 - item / p.n_splits;
+        w.split = item % p.n_splits;
+    } else {
+        const int rest = j / p.n_q_tiles;
+        w.q_tile = p.n_q_tiles - 1 - j % p.n_q_tiles;
+        head_local = rest % hh;
+        w.split = rest / hh;
+    }
     w.bh = head_local * 8 + xcd;
-    w.q_tile = p.n_q_tiles - 1 - item / p.n_splits;
-    w.split = item % p.n_splits;
     return w;
 }
 

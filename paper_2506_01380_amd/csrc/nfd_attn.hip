@@ -208,6 +208,8 @@ int nfd_block_causal_attn_fwd(nfd_attn_t* h, const void* q, const void* k, const
     p.D = D;
     p.n_q_tiles = pl.n_q_tiles;
     p.n_splits = pl.n_splits;
+    // K and V of all heads against the 256 MB last-level cache (with room for Q, O and partials)
+    p.group_q_tiles = pl.n_splits > 1 && (double)p.BH * p.Sk * nfd::mfma::kD * 2.0 * 2.0 > 192e6;
     p.scale_log2e = scale * nfd::kLog2e;
     if (pl.n_splits > 1) {
         p.part_o = (float*)h->workspace;

@@ -38,6 +38,7 @@ struct FwdParams {
     int D;
     int n_q_tiles;      // query tiles per head
     int n_splits;       // key splits per query tile
+    int group_q_tiles;  // split launches: 1 = query tiles of one (head, split) get adjacent workgroup ids
     float scale_log2e;  // softmax scale * log2(e)
 #ifdef NFD_STAGE_TIMING
     unsigned long long* timing;  // development builds only: per-wavefront stage cycle sums
