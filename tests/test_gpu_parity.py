@@ -125,6 +125,52 @@ def test_mfma_custom_scale_and_large_scores(attn_bf16):
     assert rel <= BF16_REL_L2
 
 
+def _ramp_case(top, seed):
+    """Scores that drift with the key index: q has a constant component, k the same component
+    scaled by a ramp over the keys, so the row max moves by many powers of two from tile to tile."""
+    B, H, T, D, F = 1, 2, 96, 64, 6
+    q, k, v = wl.make_qkv(B, H, D, T, F, F, F, "bf16", seed=seed)
+    ramp = np.linspace(0.0, top, F * T)  # score drift of `top` natural units over 576 keys (9 tiles)
+    q[..., 0] = 8.0
+    k[..., 0] = ramp[None, None, :]
+    return B, H, T, D, F, wl.round_to_bf16(q), wl.round_to_bf16(k), v
+
+
+def test_mfma_scores_rising_with_key_index(attn_bf16):
+    """Every later tile outgrows the reference max of the earlier ones: the exact pass (tile max,
+    rescale of the accumulators, P formed again) runs on every tile."""
+    B, H, T, D, F, q, k, v = _ramp_case(100.0, wl.BASE_SEED + 310)  # 16 powers of two per tile
+    got = run_hip(attn_bf16, q, k, v, T, F, F, "bf16")
+    ref = orc.block_causal_attn(q, k, v, T)
+    check_bf16(got, ref, "rising scores")
+
+
+def test_mfma_scores_falling_with_key_index(attn_bf16):
+    """The first tile holds the max; later tiles are formed against a reference far above them and
+    their weights underflow towards zero without ever triggering the exact pass."""
+    B, H, T, D, F, q, k, v = _ramp_case(-40.0, wl.BASE_SEED + 311)
+    got = run_hip(attn_bf16, q, k, v, T, F, F, "bf16")
+    ref = orc.block_causal_attn(q, k, v, T)
+    check_bf16(got, ref, "falling scores")
+
+
+def test_mfma_scores_just_below_and_above_the_redo_limit(attn_bf16):
+    """One key per row sits 2^14..2^16 above the reference set by the first tile: tile sums land on
+    both sides of the limit that decides between the stale reference and the exact pass."""
+    B, H, T, D, F = 1, 1, 64, 64, 4
+    q, k, v = wl.make_qkv(B, H, D, T, F, F, F, "bf16", seed=wl.BASE_SEED + 312)
+    q[:] = 0.0
+    k[:] = 0.0
+    q[..., 0] = 1.0
+    # scores are scale * k[...,0] = k/8; a score of x natural units is x*log2(e) powers of two
+    for j, pw in zip((70, 135, 200), (14.0, 15.0, 16.0)):
+        k[0, 0, j, 0] = 8.0 * pw / np.log2(np.e)
+    q, k = wl.round_to_bf16(q), wl.round_to_bf16(k)
+    got = run_hip(attn_bf16, q, k, v, T, F, F, "bf16")
+    ref = orc.block_causal_attn(q, k, v, T)
+    check_bf16(got, ref, "redo limit")
+
+
 def test_mfma_uniform_scores_mean_of_visible_v(attn_bf16):
     """Q = 0: the output is the mean of the visible V rows (closed form), checked on the device path."""
     B, H, T, D, kvf, qf = 1, 2, 48, 64, 6, 3
