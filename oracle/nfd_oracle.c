@@ -25,7 +25,10 @@
  * closed form (mean of visible V), future-perturbation invariance, cached /
  * speculative forms equal to the tail rows of the full form, visible-pair
  * count closed form, permutation and convexity invariants, one-hot limit and
- * large-magnitude stability.
+ * large-magnitude stability; for the rotary embedding: complex-multiplication
+ * form of textbook 1-D RoPE, identity at the origin, norm preservation,
+ * dependence of rotated dot products on position differences only, section
+ * independence, quarter-turn closed form.
  */
 #include <math.h>
 #include <stdint.h>
@@ -134,6 +137,69 @@ int nfd_oracle_kvcache_append(double *cache, const double *fresh, int B, int H,
         for (int64_t f = 0; f < n_frames; ++f)
             memcpy(cache + (bh * F + frame_pos + f) * rowsz,
                    fresh + (bh * n_frames + f) * rowsz, (size_t)rowsz * sizeof(double));
+    return 0;
+}
+
+/*
+ * 3D rotary position embedding of the queries and keys of n_frames new frames,
+ * with the rotated keys and the (unchanged) values written into the cache
+ * (Sec. 3.1, paragraph "3D Positional Embedding": the head dimension of query
+ * and key tokens is separated into [n_T, n_H, n_W]; rotary frequency
+ * embeddings are computed for each axis separately and concatenated along the
+ * last dimension; Appendix B "KV Caching" for the cache write).
+ *
+ * Readings where the paper is silent:
+ *  - a token's position is (t, y, x): t = t_offset + frame_pos + its frame
+ *    among the new ones, and (y, x) = (token / grid_w, token % grid_w) on the
+ *    grid_h x grid_w latent grid, T = grid_h * grid_w, row-major;
+ *  - inside the section of an axis of width n the feature pairs are the
+ *    ADJACENT ones (2i, 2i+1), i = 0 .. n/2-1, pair i turning by the angle
+ *    position * theta^(-2i/n);
+ *  - the rotation is the counter-clockwise one:
+ *    (a, b) -> (a cos - b sin, a sin + b cos).
+ * The sections lie in the order T, H, W along the head dimension; a section of
+ * width 0 is allowed; every width is even; n_t + n_h + n_w = D.
+ *
+ * q, q_out : [B, H, n_frames*T, D]       k_new, v_new : [B, H, n_frames*T, D]
+ * k_cache, v_cache : [B, H, F*T, D]
+ */
+int nfd_oracle_rope_kvcache_append(const double *q, double *q_out, double *k_cache, double *v_cache,
+                                   const double *k_new, const double *v_new, int B, int H, int F,
+                                   int T, int D, int frame_pos, int n_frames, int t_offset,
+                                   int grid_h, int grid_w, int n_t, int n_h, int n_w, double theta)
+{
+    if (!q || !q_out || !k_cache || !v_cache || !k_new || !v_new) return -1;
+    if (B < 1 || H < 1 || T < 1 || D < 1 || n_frames < 0 || frame_pos < 0) return -1;
+    if (frame_pos + n_frames > F) return -1;
+    if (grid_h < 1 || grid_w < 1 || (int64_t)grid_h * grid_w != T) return -1;
+    if (n_t < 0 || n_h < 0 || n_w < 0 || (n_t | n_h | n_w) & 1 || n_t + n_h + n_w != D) return -1;
+    if (!(theta > 0.0)) return -1;
+    const int width[3] = {n_t, n_h, n_w};
+    for (int64_t bh = 0; bh < (int64_t)B * H; ++bh)
+        for (int f = 0; f < n_frames; ++f)
+            for (int tok = 0; tok < T; ++tok) {
+                const double pos[3] = {(double)(t_offset + frame_pos + f), (double)(tok / grid_w),
+                                       (double)(tok % grid_w)};
+                const int64_t src = ((bh * n_frames + f) * T + tok) * D;
+                const int64_t dst = ((bh * F + frame_pos + f) * T + tok) * D;
+                int d0 = 0;
+                for (int ax = 0; ax < 3; ++ax) {
+                    const int n = width[ax];
+                    for (int i = 0; i < n / 2; ++i) {
+                        const double ang = pos[ax] * pow(theta, -2.0 * (double)i / (double)n);
+                        const double cs = cos(ang), sn = sin(ang);
+                        const int e = d0 + 2 * i;
+                        const double qa = q[src + e], qb = q[src + e + 1];
+                        const double ka = k_new[src + e], kb = k_new[src + e + 1];
+                        q_out[src + e] = qa * cs - qb * sn;
+                        q_out[src + e + 1] = qa * sn + qb * cs;
+                        k_cache[dst + e] = ka * cs - kb * sn;
+                        k_cache[dst + e + 1] = ka * sn + kb * cs;
+                    }
+                    d0 += n;
+                }
+                for (int e = 0; e < D; ++e) v_cache[dst + e] = v_new[src + e];
+            }
     return 0;
 }
 

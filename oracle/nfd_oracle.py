@@ -44,6 +44,8 @@ def _load():
         lib.nfd_oracle_block_causal_attn.restype = ctypes.c_int
         lib.nfd_oracle_kvcache_append.argtypes = [dp, dp] + [ctypes.c_int] * 7
         lib.nfd_oracle_kvcache_append.restype = ctypes.c_int
+        lib.nfd_oracle_rope_kvcache_append.argtypes = [dp] * 6 + [ctypes.c_int] * 13 + [ctypes.c_double]
+        lib.nfd_oracle_rope_kvcache_append.restype = ctypes.c_int
         lib.nfd_oracle_visible_pairs.argtypes = [ctypes.c_int] * 3
         lib.nfd_oracle_visible_pairs.restype = ctypes.c_int64
         _lib = lib
@@ -107,6 +109,25 @@ def kvcache_append(cache, fresh, T, frame_pos):
     if rc != 0:
         raise ValueError("oracle rejected the arguments (rc=%d)" % rc)
     return cache
+
+
+def rope_kvcache_append(q, k_cache, v_cache, k_new, v_new, T, frame_pos, grid, sections,
+                        theta=10000.0, t_offset=0):
+    """3D rotary embedding of q and k_new, rotated keys and values written into the caches at
+    frame ``frame_pos`` (Sec. 3.1 "3D Positional Embedding", Appendix B).  ``grid`` = (grid_h,
+    grid_w) with grid_h * grid_w == T; ``sections`` = (n_t, n_h, n_w) summing to D.
+    Returns (q_rotated, k_cache, v_cache) as new fp64 arrays; the inputs are not modified."""
+    q, k_new, v_new = _f64(q), _f64(k_new), _f64(v_new)
+    k_cache, v_cache = _f64(k_cache).copy(), _f64(v_cache).copy()
+    B, H, Sc, D = k_cache.shape
+    n_frames = k_new.shape[2] // T
+    q_out = np.empty_like(q)
+    rc = _load().nfd_oracle_rope_kvcache_append(
+        _ptr(q), _ptr(q_out), _ptr(k_cache), _ptr(v_cache), _ptr(k_new), _ptr(v_new), B, H, Sc // T, T, D,
+        frame_pos, n_frames, t_offset, grid[0], grid[1], sections[0], sections[1], sections[2], float(theta))
+    if rc != 0:
+        raise ValueError("oracle rejected the arguments (rc=%d)" % rc)
+    return q_out, k_cache, v_cache
 
 
 def visible_pairs(T, kv_frames, q_frames):
