@@ -97,6 +97,39 @@ int nfd_kvcache_append(nfd_attn_t* h, void* k_cache, void* v_cache, const void* 
                        const void* v_new, int B, int H, int F, int T, int D, int frame_pos,
                        int n_frames, void* stream);
 
+/*
+ * 3D rotary position embedding of the queries and keys of n_frames new frames, fused with the
+ * cache write: the step just before the attention call (Sec. 3.1, paragraph "3D Positional
+ * Embedding": the head dimension of query and key tokens is separated into [n_T, n_H, n_W], a
+ * rotary embedding is computed for each axis separately and the three are concatenated along the
+ * last dimension; Appendix B "KV Caching" for the cache).
+ *
+ *   token tok of new frame f sits at (t, y, x) = (t_offset + frame_pos + f, tok / grid_w, tok % grid_w)
+ *   features [0, n_t) follow t, [n_t, n_t + n_h) follow y, [n_t + n_h, D) follow x
+ *   inside a section of width n, pair (2i, 2i+1) at position p turns by p * theta^(-2i/n):
+ *       (a, b) -> (a cos - b sin, a sin + b cos)
+ *
+ * q, q_out       : [B, H, n_frames*T, D]; q_out receives the rotated queries and may be q itself
+ * k_new, v_new   : [B, H, n_frames*T, D]
+ * k_cache, v_cache : [B, H, F*T, D]; frames [frame_pos, frame_pos + n_frames) of every head receive the
+ *                  rotated keys and the unchanged values
+ * T must equal grid_h * grid_w; n_t, n_h, n_w are even, >= 0 and sum to D; theta > 0 (theta <= 0
+ * selects 10000); t_offset shifts the temporal positions (a sliding context window).
+ * Angles are formed in fp64, the rotation in fp32, the result rounded to the handle's dtype (RNE).
+ * n_frames == 0 is a no-op.  Errors, in this order: NFD_ERR_NULL, NFD_ERR_SHAPE (also a grid or
+ * section mismatch), NFD_ERR_CAPACITY, NFD_ERR_UNSUPPORTED (D > 256), NFD_ERR_HIP.
+ * Ownership as for the other calls: the library keeps no reference.
+ */
+int nfd_rope_kvcache_append(nfd_attn_t* h, const void* q, void* q_out, void* k_cache, void* v_cache,
+                            const void* k_new, const void* v_new, int B, int H, int F, int T, int D,
+                            int frame_pos, int n_frames, int t_offset, int grid_h, int grid_w, int n_t,
+                            int n_h, int n_w, float theta, void* stream);
+
+/* The argument checks of nfd_rope_kvcache_append that do not need pointers, same order and codes
+ * (host only, no HIP call). */
+int nfd_rope_check_args(nfd_dtype_t dtype, int B, int H, int F, int T, int D, int frame_pos, int n_frames,
+                        int grid_h, int grid_w, int n_t, int n_h, int n_w);
+
 /* Free the handle and its workspace.  NULL is accepted. */
 int nfd_attn_destroy(nfd_attn_t* h);
 

@@ -24,6 +24,7 @@ _ERR_NAMES = {
 EXPORTS = (
     "nfd_attn_create", "nfd_block_causal_attn_fwd", "nfd_kvcache_append", "nfd_attn_destroy",
     "nfd_last_error", "nfd_attn_check_args", "nfd_attn_plan", "nfd_attn_visible_pairs",
+    "nfd_rope_kvcache_append", "nfd_rope_check_args",
 )
 
 
@@ -65,6 +66,10 @@ def lib():
         L.nfd_block_causal_attn_fwd.restype = ci
         L.nfd_kvcache_append.argtypes = [vp, vp, vp, vp, vp] + [ci] * 7 + [vp]
         L.nfd_kvcache_append.restype = ci
+        L.nfd_rope_kvcache_append.argtypes = [vp] * 7 + [ci] * 13 + [cf, vp]
+        L.nfd_rope_kvcache_append.restype = ci
+        L.nfd_rope_check_args.argtypes = [ci] * 13
+        L.nfd_rope_check_args.restype = ci
         L.nfd_attn_destroy.argtypes = [vp]
         L.nfd_attn_destroy.restype = ci
         L.nfd_last_error.argtypes = [vp]
@@ -122,6 +127,18 @@ def nfd_kvcache_append(h, k_cache, v_cache, k_new, v_new, B, H, F, T, D, frame_p
     _check(rc, "nfd_kvcache_append", h)
 
 
+def nfd_rope_kvcache_append(h, q, q_out, k_cache, v_cache, k_new, v_new, B, H, F, T, D, frame_pos, n_frames,
+                            t_offset, grid_h, grid_w, n_t, n_h, n_w, theta=0.0, stream=None):
+    rc = lib().nfd_rope_kvcache_append(h, _addr(q), _addr(q_out), _addr(k_cache), _addr(v_cache), _addr(k_new),
+                                       _addr(v_new), B, H, F, T, D, frame_pos, n_frames, t_offset, grid_h, grid_w,
+                                       n_t, n_h, n_w, theta, _stream(stream))
+    _check(rc, "nfd_rope_kvcache_append", h)
+
+
+def nfd_rope_check_args(dtype, B, H, F, T, D, frame_pos, n_frames, grid_h, grid_w, n_t, n_h, n_w):
+    return lib().nfd_rope_check_args(dtype, B, H, F, T, D, frame_pos, n_frames, grid_h, grid_w, n_t, n_h, n_w)
+
+
 def nfd_attn_destroy(h):
     _check(lib().nfd_attn_destroy(h), "nfd_attn_destroy")
 
@@ -176,6 +193,20 @@ class Attention:
         B, H, Sc, D = k_cache.shape
         n_frames = k_new.shape[2] // T
         nfd_kvcache_append(self.h, k_cache, v_cache, k_new, v_new, B, H, Sc // T, T, D, frame_pos, n_frames, stream)
+
+    def rope_append(self, q, k_cache, v_cache, k_new, v_new, T, frame_pos, grid, sections, theta=0.0,
+                    t_offset=0, q_out=None, stream=None):
+        """Rotate q and k_new (3D rotary embedding), write rotated keys and values into the caches.
+        Returns the rotated queries (q itself when q_out is q)."""
+        import torch
+        B, H, Sc, D = k_cache.shape
+        n_frames = k_new.shape[2] // T
+        if q_out is None:
+            q_out = torch.empty_like(q)
+        nfd_rope_kvcache_append(self.h, q, q_out, k_cache, v_cache, k_new, v_new, B, H, Sc // T, T, D, frame_pos,
+                                n_frames, t_offset, grid[0], grid[1], sections[0], sections[1], sections[2], theta,
+                                stream)
+        return q_out
 
     def close(self):
         if self.h is not None:

@@ -114,4 +114,76 @@ kvcache_append_elem(E* __restrict__ kc, E* __restrict__ vc, const E* __restrict_
     }
 }
 
+
+// ---------------------------------------------------------------------------------------------
+// 3D rotary position embedding of the queries and keys of the new frames, fused with the cache
+// write (Sec. 3.1 "3D Positional Embedding": the head dimension is separated into [n_T, n_H, n_W],
+// one rotary embedding per axis, concatenated; Appendix B for the cache).  The rotation of feature
+// pair (2i, 2i+1) of an axis section of width n at position p is by the angle p * theta^(-2i/n),
+// counter-clockwise.  Pure streaming work: q in -> q out, k -> cache, v -> cache.
+//
+// One thread owns VEC consecutive features of one (frame, token) and walks over a range of heads:
+// the cosines and sines depend on the position only, so they are computed once (in fp64: angles
+// reach hundreds of radians) and reused for every head.  Consecutive threads cover consecutive
+// 16-byte chunks of consecutive tokens, i.e. contiguous memory inside each head.
+constexpr int kRopeMaxPairs = 128;  // D <= 256
+struct RopeTable {
+    double inv_freq[kRopeMaxPairs];     // theta^(-2i/n) of every feature pair, in head-dimension order
+    unsigned char axis[kRopeMaxPairs];  // 0 = frame index, 1 = grid row, 2 = grid column
+};
+struct RopeParams {
+    int BH, F, T, D;
+    int frame_pos, n_frames;
+    int t_pos0;            // temporal position of the first new frame
+    int grid_w;
+    int heads_per_thread;  // blockIdx.y selects a range of heads
+};
+
+template <typename E, int VEC>
+__global__ void __launch_bounds__(256)
+rope_kvcache_append(const E* q, E* q_out, E* __restrict__ kc, E* __restrict__ vc,
+                    const E* __restrict__ kn, const E* __restrict__ vn, RopeParams rp, RopeTable tab) {
+    typedef __attribute__((ext_vector_type(VEC))) E vec_t;
+    const int chunks = rp.D / VEC;
+    const int64_t items = (int64_t)rp.n_frames * rp.T * chunks;
+    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= items) return;
+    const int chunk = (int)(idx % chunks);
+    const int64_t row = idx / chunks;  // (new frame, token)
+    const int f = (int)(row / rp.T), tok = (int)(row % rp.T);
+    const int pos[3] = {rp.t_pos0 + f, tok / rp.grid_w, tok % rp.grid_w};
+    float cs[VEC / 2], sn[VEC / 2];
+#pragma unroll
+    for (int j = 0; j < VEC / 2; ++j) {
+        const int p = chunk * (VEC / 2) + j;
+        const double ang = (double)pos[tab.axis[p]] * tab.inv_freq[p];
+        double s, c;
+        sincos(ang, &s, &c);
+        cs[j] = (float)c;
+        sn[j] = (float)s;
+    }
+    const int bh0 = blockIdx.y * rp.heads_per_thread;
+    const int bh1 = min(bh0 + rp.heads_per_thread, rp.BH);
+    for (int bh = bh0; bh < bh1; ++bh) {
+        const int64_t src = ((int64_t)bh * rp.n_frames * rp.T + row) * rp.D + chunk * VEC;
+        const int64_t dst = (((int64_t)bh * rp.F + rp.frame_pos) * rp.T + row) * rp.D + chunk * VEC;
+        const vec_t qv = *(const vec_t*)(q + src);
+        const vec_t kv = *(const vec_t*)(kn + src);
+        const vec_t vv = *(const vec_t*)(vn + src);
+        vec_t qo, ko;
+#pragma unroll
+        for (int j = 0; j < VEC / 2; ++j) {
+            const float qa = (float)qv[2 * j], qb = (float)qv[2 * j + 1];
+            const float ka = (float)kv[2 * j], kb = (float)kv[2 * j + 1];
+            qo[2 * j] = (E)(qa * cs[j] - qb * sn[j]);
+            qo[2 * j + 1] = (E)(qa * sn[j] + qb * cs[j]);
+            ko[2 * j] = (E)(ka * cs[j] - kb * sn[j]);
+            ko[2 * j + 1] = (E)(ka * sn[j] + kb * cs[j]);
+        }
+        *(vec_t*)(q_out + src) = qo;
+        *(vec_t*)(kc + dst) = ko;
+        *(vec_t*)(vc + dst) = vv;
+    }
+}
+
 }  // namespace nfd

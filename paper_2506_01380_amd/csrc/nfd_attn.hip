@@ -273,4 +273,77 @@ int nfd_kvcache_append(nfd_attn_t* h, void* k_cache, void* v_cache, const void* 
     return check_hip(h, hipGetLastError(), "kvcache append launch");
 }
 
+int nfd_rope_check_args(nfd_dtype_t dtype, int B, int H, int F, int T, int D, int frame_pos, int n_frames,
+                        int grid_h, int grid_w, int n_t, int n_h, int n_w) {
+    if (B < 1 || H < 1 || F < 1 || T < 1 || D < 1 || n_frames < 0 || frame_pos < 0) return NFD_ERR_SHAPE;
+    if (grid_h < 1 || grid_w < 1 || (int64_t)grid_h * grid_w != T) return NFD_ERR_SHAPE;
+    if (n_t < 0 || n_h < 0 || n_w < 0 || ((n_t | n_h | n_w) & 1) || (int64_t)n_t + n_h + n_w != D) return NFD_ERR_SHAPE;
+    if ((int64_t)frame_pos + n_frames > F) return NFD_ERR_CAPACITY;
+    if (dtype != NFD_BF16 && dtype != NFD_FP32) return NFD_ERR_UNSUPPORTED;
+    if (D > 2 * nfd::kRopeMaxPairs) return NFD_ERR_UNSUPPORTED;
+    if ((int64_t)F * T > (int64_t)1 << 30 || (int64_t)B * H > (int64_t)1 << 24) return NFD_ERR_UNSUPPORTED;
+    return NFD_OK;
+}
+
+int nfd_rope_kvcache_append(nfd_attn_t* h, const void* q, void* q_out, void* k_cache, void* v_cache,
+                            const void* k_new, const void* v_new, int B, int H, int F, int T, int D,
+                            int frame_pos, int n_frames, int t_offset, int grid_h, int grid_w, int n_t,
+                            int n_h, int n_w, float theta, void* stream) {
+    if (!h) return NFD_ERR_NULL;
+    if (!q || !q_out || !k_cache || !v_cache || !k_new || !v_new) return fail(h, NFD_ERR_NULL, "tensors must be non-null");
+    const int rc = nfd_rope_check_args(h->dtype, B, H, F, T, D, frame_pos, n_frames, grid_h, grid_w, n_t, n_h, n_w);
+    if (rc != NFD_OK) return fail(h, rc, "invalid rotary-embedding arguments");
+    if (n_frames == 0) return NFD_OK;
+    const double th = theta > 0.f ? (double)theta : 10000.0;
+    nfd::RopeTable tab{};
+    {
+        const int width[3] = {n_t, n_h, n_w};
+        int p = 0;
+        for (int ax = 0; ax < 3; ++ax)
+            for (int i = 0; i < width[ax] / 2; ++i, ++p) {
+                tab.inv_freq[p] = std::pow(th, -2.0 * (double)i / (double)width[ax]);
+                tab.axis[p] = (unsigned char)ax;
+            }
+    }
+    nfd::RopeParams rp{};
+    rp.BH = B * H; rp.F = F; rp.T = T; rp.D = D;
+    rp.frame_pos = frame_pos; rp.n_frames = n_frames;
+    rp.t_pos0 = t_offset + frame_pos;
+    rp.grid_w = grid_w;
+    const size_t es = elem_size(h->dtype);
+    {   // a feature pair is the smallest unit a thread loads
+        const uintptr_t any = (uintptr_t)q | (uintptr_t)q_out | (uintptr_t)k_cache | (uintptr_t)v_cache | (uintptr_t)k_new | (uintptr_t)v_new;
+        if (any % (2 * es) != 0) return fail(h, NFD_ERR_UNSUPPORTED, "tensors must be aligned to one feature pair");
+    }
+    const bool aligned = ((uintptr_t)q % 16 == 0) && ((uintptr_t)q_out % 16 == 0) && ((uintptr_t)k_cache % 16 == 0) &&
+                         ((uintptr_t)v_cache % 16 == 0) && ((uintptr_t)k_new % 16 == 0) && ((uintptr_t)v_new % 16 == 0);
+    const int wide = (int)(16 / es);  // features per 16-byte chunk
+    const int vec = (aligned && D % wide == 0) ? wide : 2;
+    const int64_t items = (int64_t)n_frames * T * (D / vec);
+    const int64_t gx = (items + 255) / 256;
+    // enough workgroups to fill the chip, otherwise as many heads per thread as possible (the
+    // cosines and sines are shared by all heads)
+    const int64_t want_y = std::min<int64_t>(rp.BH, std::max<int64_t>(1, ((int64_t)h->num_cus * 8 + gx - 1) / gx));
+    rp.heads_per_thread = (int)((rp.BH + want_y - 1) / want_y);
+    const unsigned gy = (unsigned)((rp.BH + rp.heads_per_thread - 1) / rp.heads_per_thread);
+    const dim3 grid((unsigned)gx, gy), block(256);
+    hipStream_t st = (hipStream_t)stream;
+    if (h->dtype == NFD_BF16) {
+        if (vec == 8)
+            hipLaunchKernelGGL((nfd::rope_kvcache_append<__bf16, 8>), grid, block, 0, st, (const __bf16*)q, (__bf16*)q_out,
+                               (__bf16*)k_cache, (__bf16*)v_cache, (const __bf16*)k_new, (const __bf16*)v_new, rp, tab);
+        else
+            hipLaunchKernelGGL((nfd::rope_kvcache_append<__bf16, 2>), grid, block, 0, st, (const __bf16*)q, (__bf16*)q_out,
+                               (__bf16*)k_cache, (__bf16*)v_cache, (const __bf16*)k_new, (const __bf16*)v_new, rp, tab);
+    } else {
+        if (vec == 4)
+            hipLaunchKernelGGL((nfd::rope_kvcache_append<float, 4>), grid, block, 0, st, (const float*)q, (float*)q_out,
+                               (float*)k_cache, (float*)v_cache, (const float*)k_new, (const float*)v_new, rp, tab);
+        else
+            hipLaunchKernelGGL((nfd::rope_kvcache_append<float, 2>), grid, block, 0, st, (const float*)q, (float*)q_out,
+                               (float*)k_cache, (float*)v_cache, (const float*)k_new, (const float*)v_new, rp, tab);
+    }
+    return check_hip(h, hipGetLastError(), "rotary embedding launch");
+}
+
 }  // extern "C"

@@ -40,6 +40,20 @@ def test_check_args_codes(args, code):
     assert nb.nfd_attn_check_args(nb.NFD_BF16, **args) == code
 
 
+@pytest.mark.parametrize("args,code", [
+    (dict(B=1, H=16, F=40, T=336, D=64, frame_pos=32, n_frames=1, grid_h=24, grid_w=14, n_t=16, n_h=24, n_w=24), nb.NFD_OK),
+    (dict(B=1, H=16, F=40, T=336, D=64, frame_pos=32, n_frames=0, grid_h=24, grid_w=14, n_t=64, n_h=0, n_w=0), nb.NFD_OK),
+    (dict(B=1, H=16, F=40, T=336, D=64, frame_pos=32, n_frames=1, grid_h=24, grid_w=13, n_t=16, n_h=24, n_w=24), nb.NFD_ERR_SHAPE),
+    (dict(B=1, H=16, F=40, T=336, D=64, frame_pos=32, n_frames=1, grid_h=24, grid_w=14, n_t=15, n_h=25, n_w=24), nb.NFD_ERR_SHAPE),
+    (dict(B=1, H=16, F=40, T=336, D=64, frame_pos=32, n_frames=1, grid_h=24, grid_w=14, n_t=16, n_h=24, n_w=22), nb.NFD_ERR_SHAPE),
+    (dict(B=1, H=16, F=40, T=336, D=64, frame_pos=-1, n_frames=1, grid_h=24, grid_w=14, n_t=16, n_h=24, n_w=24), nb.NFD_ERR_SHAPE),
+    (dict(B=1, H=16, F=40, T=336, D=64, frame_pos=39, n_frames=2, grid_h=24, grid_w=14, n_t=16, n_h=24, n_w=24), nb.NFD_ERR_CAPACITY),
+    (dict(B=1, H=1, F=2, T=4, D=512, frame_pos=0, n_frames=1, grid_h=2, grid_w=2, n_t=512, n_h=0, n_w=0), nb.NFD_ERR_UNSUPPORTED),
+])
+def test_rope_check_args_codes(args, code):
+    assert nb.nfd_rope_check_args(nb.NFD_BF16, **args) == code
+
+
 def test_bad_dtype_is_unsupported():
     assert nb.nfd_attn_check_args(7, 1, 1, 1, 1, 64, 1, 1) == nb.NFD_ERR_UNSUPPORTED
 
