@@ -29,6 +29,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of the oracle sample")
     ap.add_argument("--all", action="store_true", help="also time the other workloads (reported on stderr)")
+    ap.add_argument("--rope", action="store_true",
+                    help="also time the fused 3D rotary embedding + cache write on the workload's new frames (stderr and 'pre_op')")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a 1 GiB device copy a few times (a kernel of known HBM bytes, for scaling profiler counters)")
     args = ap.parse_args()
@@ -97,6 +99,46 @@ def main():
         torch.cuda.synchronize()
         del kc, vc, kn, vn
 
+    def time_rope(name, steps, warmup):
+        """The step before the attention call: rotate q and k of the workload's query frames, write k and v
+        into the cache.  HBM-bound streaming: 3 tensors in, 3 out."""
+        c = wl.CONFIGS[name]
+        B, H, D, T, kvf, qf, F = (c[x] for x in ("B", "H", "D", "T", "kv_frames", "q_frames", "F"))
+        grid = (24, T // 24)          # 24 x 14 latent grid at T = 336, 24 x 24 at T = 576
+        sections = (16, 24, 24)       # [n_T, n_H, n_W] of a 64-wide head
+        gen = torch.Generator(device="cuda").manual_seed(c["seed"] + 5)
+        mk = lambda *s: torch.randn(*s, device="cuda", generator=gen, dtype=torch.float32).to(torch.bfloat16)
+        sets = []
+        for _ in range(4):
+            sets.append((mk(B, H, qf * T, D), mk(B, H, qf * T, D), mk(B, H, qf * T, D),
+                         torch.empty(B, H, qf * T, D, device="cuda", dtype=torch.bfloat16),
+                         torch.zeros(B, H, F * T, D, device="cuda", dtype=torch.bfloat16),
+                         torch.zeros(B, H, F * T, D, device="cuda", dtype=torch.bfloat16)))
+
+        def step(i):
+            q, kn, vn, qo, kc, vc = sets[i % len(sets)]
+            nb.nfd_rope_kvcache_append(attn.h, q, qo, kc, vc, kn, vn, B, H, F, T, D, kvf - qf, qf, 0,
+                                       grid[0], grid[1], sections[0], sections[1], sections[2], 10000.0)
+
+        for i in range(warmup):
+            step(i)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(steps):
+            step(i)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / steps
+        nbytes = 6 * B * H * qf * T * D * 2  # q, k, v read; q, k, v written
+        return dict(kernel="rope_kvcache_append", workload=name, us_per_call=round(ms * 1e3, 2), bytes=nbytes,
+                    gbs=round(nbytes / ms * 1e-6, 1), frac_hbm_peak=round(nbytes / ms * 1e-6 / PEAK_HBM_GBS, 4))
+
+    pre_op = None
+    if args.rope:
+        pre_op = time_rope(args.workload, args.steps, args.warmup)
+        print(json.dumps(pre_op), file=sys.stderr, flush=True)
+
     others = []
     if args.all:
         for name in wl.CONFIGS:
@@ -160,6 +202,8 @@ def main():
                      "kernel": "attn_fwd_bf16_d64"},
         "cpu_baseline": cpu,
     }
+    if pre_op:
+        line["pre_op"] = pre_op
     if others:
         line["other_workloads"] = [{k: (round(v, 4) if isinstance(v, float) else v) for k, v in r.items()
                                     if k in ("workload", "ms_per_step", "tflops", "gbs", "frames_per_s")} for r in others]
