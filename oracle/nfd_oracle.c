@@ -122,6 +122,113 @@ int nfd_oracle_block_causal_attn(const double *q, const double *k, const double 
 }
 
 /*
+ * Gradients of the attention above with respect to q, k and v, for an upstream
+ * gradient dout of the output (the paper trains through this attention:
+ * Sec. 3.2 "Training"; the mask is the one of Sec. 3.1).  Written out from the
+ * definition, element by element:
+ *
+ *   p_ij   = M_ij exp(s_ij) / sum_l M_il exp(s_il)          (softmax over visible keys)
+ *   dv_j   = sum_i p_ij dout_i
+ *   dp_ij  = <dout_i, v_j>
+ *   ds_ij  = p_ij (dp_ij - sum_l p_il dp_il)                 (Jacobian of the softmax)
+ *   dq_i   = scale sum_j ds_ij k_j          dk_j = scale sum_i ds_ij q_i
+ *
+ * dq : [B, H, q_frames*T, D]; dk, dv : [B, H, F*T, D] (rows at and past kv_frames*T are set to 0);
+ * lse (optional, may be NULL) : [B, H, q_frames*T] = log sum_l M_il exp(s_il).
+ */
+int nfd_oracle_block_causal_attn_bwd(const double *q, const double *k, const double *v,
+                                     const double *dout, double *dq, double *dk, double *dv,
+                                     double *lse, int B, int H, int F, int T, int D, int kv_frames,
+                                     int q_frames, double scale)
+{
+    if (!q || !k || !v || !dout || !dq || !dk || !dv) return -1;
+    if (B < 1 || H < 1 || T < 1 || D < 1 || q_frames < 1) return -1;
+    if (q_frames > kv_frames || kv_frames > F) return -1;
+    const int64_t Sq = (int64_t)q_frames * T, Sk = (int64_t)kv_frames * T, Scap = (int64_t)F * T;
+    const int64_t P = (int64_t)kv_frames - q_frames;
+    const int64_t BH = (int64_t)B * H;
+    double *L = (double *)malloc((size_t)(BH * Sq) * sizeof(double));   /* log of the row's softmax denominator */
+    double *G = (double *)malloc((size_t)(BH * Sq) * sizeof(double));   /* sum_l p_il dp_il */
+    if (!L || !G) { free(L); free(G); return -1; }
+    int failed = 0;
+
+    /* rows: p_i., dp_i., the row's Jacobian term, dq_i */
+#pragma omp parallel
+    {
+        double *p = (double *)malloc((size_t)Sk * sizeof(double));
+        double *dp = (double *)malloc((size_t)Sk * sizeof(double));
+        if (!p || !dp) {
+#pragma omp atomic write
+            failed = 1;
+        }
+#pragma omp barrier
+        if (!failed) {
+#pragma omp for collapse(2) schedule(dynamic, 8)
+            for (int64_t bh = 0; bh < BH; ++bh)
+                for (int64_t i = 0; i < Sq; ++i) {
+                    const double *qi = q + (bh * Sq + i) * D, *gi = dout + (bh * Sq + i) * D;
+                    const double *kb = k + bh * Scap * D, *vb = v + bh * Scap * D;
+                    double m = -INFINITY;
+                    for (int64_t j = 0; j < Sk; ++j) {
+                        if (!visible(i, j, T, P)) { p[j] = 0.0; continue; }
+                        double s = 0.0;
+                        for (int d = 0; d < D; ++d) s += qi[d] * kb[j * D + d];
+                        p[j] = s * scale;
+                        if (p[j] > m) m = p[j];
+                    }
+                    double denom = 0.0;
+                    for (int64_t j = 0; j < Sk; ++j)
+                        if (visible(i, j, T, P)) { p[j] = exp(p[j] - m); denom += p[j]; }
+                    double g = 0.0;
+                    for (int64_t j = 0; j < Sk; ++j) {
+                        dp[j] = 0.0;
+                        if (!visible(i, j, T, P)) continue;
+                        p[j] /= denom;
+                        for (int d = 0; d < D; ++d) dp[j] += gi[d] * vb[j * D + d];
+                        g += p[j] * dp[j];
+                    }
+                    L[bh * Sq + i] = m + log(denom);
+                    G[bh * Sq + i] = g;
+                    double *dqi = dq + (bh * Sq + i) * D;
+                    for (int d = 0; d < D; ++d) dqi[d] = 0.0;
+                    for (int64_t j = 0; j < Sk; ++j) {
+                        if (!visible(i, j, T, P)) continue;
+                        const double ds = p[j] * (dp[j] - g);
+                        for (int d = 0; d < D; ++d) dqi[d] += scale * ds * kb[j * D + d];
+                    }
+                }
+        }
+        free(p);
+        free(dp);
+    }
+
+    /* keys: dv_j and dk_j gather over the rows that see key j */
+    if (!failed) {
+#pragma omp parallel for collapse(2) schedule(dynamic, 8)
+        for (int64_t bh = 0; bh < BH; ++bh)
+            for (int64_t j = 0; j < Scap; ++j) {
+                double *dkj = dk + (bh * Scap + j) * D, *dvj = dv + (bh * Scap + j) * D;
+                for (int d = 0; d < D; ++d) { dkj[d] = 0.0; dvj[d] = 0.0; }
+                if (j >= Sk) continue;
+                const double *kj = k + (bh * Scap + j) * D, *vj = v + (bh * Scap + j) * D;
+                for (int64_t i = 0; i < Sq; ++i) {
+                    if (!visible(i, j, T, P)) continue;
+                    const double *qi = q + (bh * Sq + i) * D, *gi = dout + (bh * Sq + i) * D;
+                    double s = 0.0, dpij = 0.0;
+                    for (int d = 0; d < D; ++d) { s += qi[d] * kj[d]; dpij += gi[d] * vj[d]; }
+                    const double pij = exp(s * scale - L[bh * Sq + i]);
+                    const double ds = pij * (dpij - G[bh * Sq + i]);
+                    for (int d = 0; d < D; ++d) { dvj[d] += pij * gi[d]; dkj[d] += scale * ds * qi[d]; }
+                }
+            }
+    }
+    if (lse && !failed) memcpy(lse, L, (size_t)(BH * Sq) * sizeof(double));
+    free(L);
+    free(G);
+    return failed ? -1 : 0;
+}
+
+/*
  * KV cache write (Appendix B, "KV Caching": K/V of frames are computed once
  * and reused).  Copies n_frames new frames into the cache at frame frame_pos.
  * cache : [B, H, F*T, D]   fresh : [B, H, n_frames*T, D]

@@ -42,6 +42,8 @@ def _load():
         lib.nfd_oracle_block_causal_attn.argtypes = [dp, dp, dp, dp] + [ctypes.c_int] * 7 + [
             ctypes.c_double, ip, ctypes.c_int64]
         lib.nfd_oracle_block_causal_attn.restype = ctypes.c_int
+        lib.nfd_oracle_block_causal_attn_bwd.argtypes = [dp] * 8 + [ctypes.c_int] * 7 + [ctypes.c_double]
+        lib.nfd_oracle_block_causal_attn_bwd.restype = ctypes.c_int
         lib.nfd_oracle_kvcache_append.argtypes = [dp, dp] + [ctypes.c_int] * 7
         lib.nfd_oracle_kvcache_append.restype = ctypes.c_int
         lib.nfd_oracle_rope_kvcache_append.argtypes = [dp] * 6 + [ctypes.c_int] * 13 + [ctypes.c_double]
@@ -96,6 +98,26 @@ def block_causal_attn(q, k, v, T, kv_frames=None, q_frames=None, scale=None, row
     if rc != 0:
         raise ValueError("oracle rejected the arguments (rc=%d)" % rc)
     return out
+
+
+def block_causal_attn_bwd(q, k, v, dout, T, kv_frames=None, q_frames=None, scale=None):
+    """Gradients (dq, dk, dv) of the block-wise causal attention for the upstream gradient ``dout``,
+    plus the per-row log of the softmax denominator: returns (dq, dk, dv, lse), all fp64.
+    dk, dv have the shape of k, v; rows past kv_frames*T are zero."""
+    q, k, v, dout = _f64(q), _f64(k), _f64(v), _f64(dout)
+    B, H, Sq, D = q.shape
+    Scap = k.shape[2]
+    q_frames = Sq // T if q_frames is None else q_frames
+    kv_frames = Scap // T if kv_frames is None else kv_frames
+    scale = 1.0 / np.sqrt(D) if scale is None else float(scale)
+    dq, dk, dv = np.empty_like(q), np.empty_like(k), np.empty_like(v)
+    lse = np.empty((B, H, Sq), dtype=np.float64)
+    rc = _load().nfd_oracle_block_causal_attn_bwd(_ptr(q), _ptr(k), _ptr(v), _ptr(dout), _ptr(dq), _ptr(dk),
+                                                  _ptr(dv), _ptr(lse), B, H, Scap // T, T, D, kv_frames,
+                                                  q_frames, scale)
+    if rc != 0:
+        raise ValueError("oracle rejected the arguments (rc=%d)" % rc)
+    return dq, dk, dv, lse
 
 
 def kvcache_append(cache, fresh, T, frame_pos):
