@@ -83,6 +83,33 @@ int nfd_block_causal_attn_fwd(nfd_attn_t* h, const void* q, const void* k, const
                               float scale, void* stream);
 
 /*
+ * The same forward, additionally writing lse[b,h,i] = log sum_{visible j} exp(scale <q_i, k_j>)
+ * (fp32, [B, H, q_frames*T]), which the backward call below consumes.  Arguments, support and
+ * errors as for nfd_block_causal_attn_fwd; lse == NULL is NFD_ERR_NULL.
+ */
+int nfd_block_causal_attn_fwd_lse(nfd_attn_t* h, const void* q, const void* k, const void* v, void* out,
+                                  float* lse, int B, int H, int F, int T, int D, int kv_frames, int q_frames,
+                                  float scale, void* stream);
+
+/*
+ * Backward of the block-wise causal attention: the paper trains through this attention (Sec. 3.2
+ * "Training"; mask of Sec. 3.1).  For the upstream gradient dout of out, with p_ij the softmax
+ * weights of the visible keys:
+ *   dv_j = sum_i p_ij dout_i      ds_ij = p_ij (<dout_i, v_j> - <dout_i, out_i>)
+ *   dq_i = scale sum_j ds_ij k_j  dk_j = scale sum_i ds_ij q_i
+ * q, out, dout, dq : [B, H, q_frames*T, D]     k, v, dk, dv : [B, H, F*T, D]     lse : [B, H, q_frames*T]
+ * out and lse are the results of nfd_block_causal_attn_fwd_lse on the same q, k, v, scale.  Of dk and
+ * dv only the first kv_frames*T rows of every head are written.  No atomics: results are
+ * bit-reproducible.  Uses the handle's workspace (4 bytes per query row).
+ * Supported: bf16, D = 64 (any B, H, T, frames); everything else NFD_ERR_UNSUPPORTED.
+ * Errors, in this order: NFD_ERR_NULL, NFD_ERR_SHAPE, NFD_ERR_CAPACITY, NFD_ERR_UNSUPPORTED,
+ * NFD_ERR_ALLOC (workspace too small), NFD_ERR_HIP.
+ */
+int nfd_block_causal_attn_bwd(nfd_attn_t* h, const void* q, const void* k, const void* v, const void* out,
+                              const void* dout, const float* lse, void* dq, void* dk, void* dv, int B, int H,
+                              int F, int T, int D, int kv_frames, int q_frames, float scale, void* stream);
+
+/*
  * Write the K and V of n_frames new frames into the cache at frame frame_pos
  * (Appendix B, "KV Caching": K/V of a frame are computed once and reused by
  * every later denoising step and frame).

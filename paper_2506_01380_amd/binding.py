@@ -25,6 +25,7 @@ EXPORTS = (
     "nfd_attn_create", "nfd_block_causal_attn_fwd", "nfd_kvcache_append", "nfd_attn_destroy",
     "nfd_last_error", "nfd_attn_check_args", "nfd_attn_plan", "nfd_attn_visible_pairs",
     "nfd_rope_kvcache_append", "nfd_rope_check_args",
+    "nfd_block_causal_attn_fwd_lse", "nfd_block_causal_attn_bwd",
 )
 
 
@@ -64,6 +65,10 @@ def lib():
         L.nfd_attn_create.restype = ci
         L.nfd_block_causal_attn_fwd.argtypes = [vp, vp, vp, vp, vp] + [ci] * 7 + [cf, vp]
         L.nfd_block_causal_attn_fwd.restype = ci
+        L.nfd_block_causal_attn_fwd_lse.argtypes = [vp] * 6 + [ci] * 7 + [cf, vp]
+        L.nfd_block_causal_attn_fwd_lse.restype = ci
+        L.nfd_block_causal_attn_bwd.argtypes = [vp] * 10 + [ci] * 7 + [cf, vp]
+        L.nfd_block_causal_attn_bwd.restype = ci
         L.nfd_kvcache_append.argtypes = [vp, vp, vp, vp, vp] + [ci] * 7 + [vp]
         L.nfd_kvcache_append.restype = ci
         L.nfd_rope_kvcache_append.argtypes = [vp] * 7 + [ci] * 13 + [cf, vp]
@@ -119,6 +124,20 @@ def nfd_block_causal_attn_fwd(h, q, k, v, out, B, H, F, T, D, kv_frames, q_frame
     rc = lib().nfd_block_causal_attn_fwd(h, _addr(q), _addr(k), _addr(v), _addr(out), B, H, F, T, D,
                                          kv_frames, q_frames, scale, _stream(stream))
     _check(rc, "nfd_block_causal_attn_fwd", h)
+
+
+def nfd_block_causal_attn_fwd_lse(h, q, k, v, out, lse, B, H, F, T, D, kv_frames, q_frames, scale=0.0, stream=None):
+    rc = lib().nfd_block_causal_attn_fwd_lse(h, _addr(q), _addr(k), _addr(v), _addr(out), _addr(lse), B, H, F, T, D,
+                                             kv_frames, q_frames, scale, _stream(stream))
+    _check(rc, "nfd_block_causal_attn_fwd_lse", h)
+
+
+def nfd_block_causal_attn_bwd(h, q, k, v, out, dout, lse, dq, dk, dv, B, H, F, T, D, kv_frames, q_frames,
+                              scale=0.0, stream=None):
+    rc = lib().nfd_block_causal_attn_bwd(h, _addr(q), _addr(k), _addr(v), _addr(out), _addr(dout), _addr(lse),
+                                         _addr(dq), _addr(dk), _addr(dv), B, H, F, T, D, kv_frames, q_frames,
+                                         scale, _stream(stream))
+    _check(rc, "nfd_block_causal_attn_bwd", h)
 
 
 def nfd_kvcache_append(h, k_cache, v_cache, k_new, v_new, B, H, F, T, D, frame_pos, n_frames, stream=None):
@@ -188,6 +207,31 @@ class Attention:
             out = torch.empty_like(q)
         nfd_block_causal_attn_fwd(self.h, q, k, v, out, B, H, F, T, D, kv_frames, q_frames, scale, stream)
         return out
+
+    def forward_lse(self, q, k, v, T, kv_frames=None, q_frames=None, scale=0.0, stream=None):
+        """Forward that also returns the per-row log-sum-exp (fp32) for the backward call."""
+        import torch
+        B, H, Sq, D = q.shape
+        F = k.shape[2] // T
+        kv_frames = F if kv_frames is None else kv_frames
+        q_frames = Sq // T if q_frames is None else q_frames
+        out = torch.empty_like(q)
+        lse = torch.empty((B, H, Sq), dtype=torch.float32, device=q.device)
+        nfd_block_causal_attn_fwd_lse(self.h, q, k, v, out, lse, B, H, F, T, D, kv_frames, q_frames, scale, stream)
+        return out, lse
+
+    def backward(self, q, k, v, out, dout, lse, T, kv_frames=None, q_frames=None, scale=0.0, stream=None):
+        """Gradients (dq, dk, dv); dk, dv have the shape of k, v (rows past kv_frames*T are zero)."""
+        import torch
+        B, H, Sq, D = q.shape
+        F = k.shape[2] // T
+        kv_frames = F if kv_frames is None else kv_frames
+        q_frames = Sq // T if q_frames is None else q_frames
+        dq = torch.empty_like(q)
+        dk, dv = torch.zeros_like(k), torch.zeros_like(v)
+        nfd_block_causal_attn_bwd(self.h, q, k, v, out, dout, lse, dq, dk, dv, B, H, F, T, D, kv_frames, q_frames,
+                                  scale, stream)
+        return dq, dk, dv
 
     def append(self, k_cache, v_cache, k_new, v_new, T, frame_pos, stream=None):
         B, H, Sc, D = k_cache.shape

@@ -84,6 +84,7 @@ attn_fwd_generic(FwdParams p) {
         const int d = lane + 64 * c;
         if (d < D) out[d] = from_f32<T>(acc[c] * inv);
     }
+    if (p.lse && lane == 0) p.lse[row_id] = (m + log2f(l)) * kLn2;
 }
 
 // Copy n_frames frames of every head into the cache at frame_pos (Appendix B, KV caching).

@@ -128,6 +128,7 @@ __device__ __forceinline__ void store_rows(const FwdParams& p, const WorkItem& w
                     const bf16x4 y = __builtin_convertvector(x, bf16x4);
                     *(bf16x4*)(og + 32 * dt + 8 * rb + 4 * h) = y;
                 }
+            if (p.lse && h == 0) p.lse[(int64_t)wi.bh * p.Sq + row[qt]] = (m_used[qt] * c + __builtin_log2f(l_row)) * kLn2;
         } else {
             const int64_t prow = ((int64_t)wi.bh * p.n_splits + wi.split) * p.Sq + row[qt];
             float* po = p.part_o + prow * kD;
@@ -467,6 +468,7 @@ attn_combine_d64(FwdParams p) {
     const f32x4 x = acc * inv;
     const bf16x4 y = __builtin_convertvector(x, bf16x4);
     *(bf16x4*)((__bf16*)p.out + r * kD + 4 * dq) = y;
+    if (p.lse && dq == 0) p.lse[r] = (m_run + __builtin_log2f(l)) * kLn2;
 }
 
 }  // namespace mfma

@@ -14,6 +14,7 @@
 
 #include "kernels_generic.hpp"
 #include "kernels_mfma.hpp"
+#include "kernels_mfma_bwd.hpp"
 
 struct nfd_attn {
     nfd_dtype_t dtype;
@@ -184,9 +185,8 @@ int nfd_attn_destroy(nfd_attn_t* h) {
 
 const char* nfd_last_error(const nfd_attn_t* h) { return h ? h->err.c_str() : "null handle"; }
 
-int nfd_block_causal_attn_fwd(nfd_attn_t* h, const void* q, const void* k, const void* v, void* out, int B,
-                              int H, int F, int T, int D, int kv_frames, int q_frames, float scale,
-                              void* stream) {
+static int fwd_impl(nfd_attn_t* h, const void* q, const void* k, const void* v, void* out, float* lse, int B,
+                    int H, int F, int T, int D, int kv_frames, int q_frames, float scale, void* stream) {
     if (!h) return NFD_ERR_NULL;
     if (!q || !k || !v || !out) return fail(h, NFD_ERR_NULL, "q, k, v and out must be non-null");
     nfd_attn_plan_t pl;
@@ -199,6 +199,7 @@ int nfd_block_causal_attn_fwd(nfd_attn_t* h, const void* q, const void* k, const
 
     nfd::FwdParams p{};
     p.q = q; p.k = k; p.v = v; p.out = out;
+    p.lse = lse;
     p.BH = B * H;
     p.Sq = q_frames * T;
     p.Sk = kv_frames * T;
@@ -235,6 +236,53 @@ int nfd_block_causal_attn_fwd(nfd_attn_t* h, const void* q, const void* k, const
         hipLaunchKernelGGL(nfd::attn_fwd_generic<__bf16>, dim3(pl.n_workgroups), dim3(nfd::kGenericWaves * 64), 0, st, p);
     }
     return check_hip(h, hipGetLastError(), "attention launch");
+}
+
+int nfd_block_causal_attn_fwd(nfd_attn_t* h, const void* q, const void* k, const void* v, void* out, int B,
+                              int H, int F, int T, int D, int kv_frames, int q_frames, float scale,
+                              void* stream) {
+    return fwd_impl(h, q, k, v, out, nullptr, B, H, F, T, D, kv_frames, q_frames, scale, stream);
+}
+
+int nfd_block_causal_attn_fwd_lse(nfd_attn_t* h, const void* q, const void* k, const void* v, void* out,
+                                  float* lse, int B, int H, int F, int T, int D, int kv_frames, int q_frames,
+                                  float scale, void* stream) {
+    if (h && !lse) return fail(h, NFD_ERR_NULL, "lse must be non-null");
+    return fwd_impl(h, q, k, v, out, lse, B, H, F, T, D, kv_frames, q_frames, scale, stream);
+}
+
+int nfd_block_causal_attn_bwd(nfd_attn_t* h, const void* q, const void* k, const void* v, const void* out,
+                              const void* dout, const float* lse, void* dq, void* dk, void* dv, int B, int H,
+                              int F, int T, int D, int kv_frames, int q_frames, float scale, void* stream) {
+    if (!h) return NFD_ERR_NULL;
+    if (!q || !k || !v || !out || !dout || !lse || !dq || !dk || !dv)
+        return fail(h, NFD_ERR_NULL, "all tensors of the backward call must be non-null");
+    const int rc = nfd_attn_check_args(h->dtype, B, H, F, T, D, kv_frames, q_frames);
+    if (rc != NFD_OK) return fail(h, rc, "invalid shape arguments");
+    if (h->dtype != NFD_BF16 || D != nfd::mfma::kD)
+        return fail(h, NFD_ERR_UNSUPPORTED, "the backward is built for bf16 and head width 64");
+    const int64_t BH = (int64_t)B * H, Sq = (int64_t)q_frames * T, Sk = (int64_t)kv_frames * T;
+    if ((size_t)(BH * Sq) * sizeof(float) > h->workspace_bytes)
+        return fail(h, NFD_ERR_ALLOC, "the per-row workspace of the backward exceeds the handle's workspace");
+    if (!(scale > 0.f)) scale = 1.0f / std::sqrt((float)D);
+
+    nfd::mfma::BwdParams p{};
+    p.q = q; p.k = k; p.v = v; p.dout = dout; p.lse = lse;
+    p.delta = (float*)h->workspace;
+    p.dq = dq; p.dk = dk; p.dv = dv;
+    p.BH = (int)BH; p.Sq = (int)Sq; p.Sk = (int)Sk; p.Scap = F * T; p.T = T; p.P = kv_frames - q_frames;
+    p.n_q_tiles = (int)((Sq + nfd::mfma::kBM - 1) / nfd::mfma::kBM);
+    p.n_k_blocks = (int)((Sk + 255) / 256);
+    p.scale = scale;
+    p.scale_log2e = scale * nfd::kLog2e;
+    hipStream_t st = (hipStream_t)stream;
+    const int64_t rows = BH * Sq;
+    const unsigned heads8 = (unsigned)(8 * ((BH + 7) / 8));
+    hipLaunchKernelGGL(nfd::mfma::attn_bwd_delta, dim3((unsigned)((rows * 8 + 255) / 256)), dim3(256), 0, st,
+                       (const __bf16*)out, (const __bf16*)dout, p.delta, rows);
+    hipLaunchKernelGGL(nfd::mfma::attn_bwd_dkdv_bf16_d64, dim3(heads8 * p.n_k_blocks), dim3(256), 0, st, p);
+    hipLaunchKernelGGL(nfd::mfma::attn_bwd_dq_bf16_d64, dim3(heads8 * p.n_q_tiles), dim3(256), 0, st, p);
+    return check_hip(h, hipGetLastError(), "backward launch");
 }
 
 int nfd_kvcache_append(nfd_attn_t* h, void* k_cache, void* v_cache, const void* k_new, const void* v_new, int B,

@@ -17,6 +17,7 @@ typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 
 constexpr float kLog2e = 1.4426950408889634f;
 // Running maxima start at a large finite negative so that (m_old - m_new) is never inf - inf.
+constexpr float kLn2 = 0.69314718055994531f;
 constexpr float kNegBig = -1.0e30f;
 
 // Launch geometry and tensor description shared by every forward kernel.
@@ -29,6 +30,7 @@ struct FwdParams {
     void* out;          // [BH, Sq, D]
     float* part_o;      // [BH, n_splits, Sq, D] un-normalised partial outputs (split launches)
     float* part_ml;     // [BH, n_splits, Sq, 2]  (running max in log2 units, running sum)
+    float* lse;         // [BH, Sq] optional: natural log of the row's softmax denominator (for the backward)
     int BH;             // B * H
     int Sq;             // q_frames * T
     int Sk;             // kv_frames * T
