@@ -29,6 +29,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of the oracle sample")
     ap.add_argument("--all", action="store_true", help="also time the other workloads (reported on stderr)")
+    ap.add_argument("--bwd", action="store_true",
+                    help="also time the training step of the attention: forward with log-sum-exp + backward (stderr and 'backward')")
     ap.add_argument("--rope", action="store_true",
                     help="also time the fused 3D rotary embedding + cache write on the workload's new frames (stderr and 'pre_op')")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -134,6 +136,50 @@ def main():
         return dict(kernel="rope_kvcache_append", workload=name, us_per_call=round(ms * 1e3, 2), bytes=nbytes,
                     gbs=round(nbytes / ms * 1e-6, 1), frac_hbm_peak=round(nbytes / ms * 1e-6 / PEAK_HBM_GBS, 4))
 
+    def time_bwd(name, steps, warmup):
+        """Forward that keeps the log-sum-exp, then the backward (delta, dk/dv, dq kernels).  FLOPs counted:
+        forward 4.D per visible pair, backward 10.D (five products), the recomputation in the second
+        backward kernel is not counted."""
+        c = wl.CONFIGS[name]
+        B, H, D, T, kvf, qf, F = (c[x] for x in ("B", "H", "D", "T", "kv_frames", "q_frames", "F"))
+        gen = torch.Generator(device="cuda").manual_seed(c["seed"] + 7)
+        mk = lambda *s: torch.randn(*s, device="cuda", generator=gen, dtype=torch.float32).to(torch.bfloat16)
+        q, k, v, g = mk(B, H, qf * T, D), mk(B, H, F * T, D), mk(B, H, F * T, D), mk(B, H, qf * T, D)
+        out = torch.empty_like(q)
+        lse = torch.empty((B, H, qf * T), dtype=torch.float32, device="cuda")
+        dq, dk, dv = torch.empty_like(q), torch.zeros_like(k), torch.zeros_like(v)
+
+        def fwd():
+            nb.nfd_block_causal_attn_fwd_lse(attn.h, q, k, v, out, lse, B, H, F, T, D, kvf, qf)
+
+        def bwd():
+            nb.nfd_block_causal_attn_bwd(attn.h, q, k, v, out, g, lse, dq, dk, dv, B, H, F, T, D, kvf, qf)
+
+        def timed(fn):
+            for _ in range(warmup):
+                fn()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(steps):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / steps
+
+        fwd()
+        ms_f, ms_b = timed(fwd), timed(bwd)
+        fl = nb.unmasked_flops(B, H, D, T, kvf, qf)
+        return dict(kernel="attn_bwd_dkdv_bf16_d64 + attn_bwd_dq_bf16_d64 + attn_bwd_delta", workload=name,
+                    fwd_lse_ms=round(ms_f, 5), bwd_ms=round(ms_b, 5), bwd_tflops=round(2.5 * fl / ms_b * 1e-9, 2),
+                    bwd_frac_mfma_peak=round(2.5 * fl / ms_b * 1e-9 / PEAK_BF16_TFLOPS, 4),
+                    fwd_bwd_tflops=round(3.5 * fl / (ms_f + ms_b) * 1e-9, 2))
+
+    backward = None
+    if args.bwd:
+        backward = time_bwd(args.workload, max(5, args.steps // 4), max(2, args.warmup // 4))
+        print(json.dumps(backward), file=sys.stderr, flush=True)
+
     pre_op = None
     if args.rope:
         pre_op = time_rope(args.workload, args.steps, args.warmup)
@@ -202,6 +248,8 @@ def main():
                      "kernel": "attn_fwd_bf16_d64"},
         "cpu_baseline": cpu,
     }
+    if backward:
+        line["backward"] = backward
     if pre_op:
         line["pre_op"] = pre_op
     if others:

@@ -84,6 +84,17 @@ def test_backward_every_element(attn, B, H, T, kvf, qf, F):
     assert np.abs(got[3] - ref[3]).max() <= 2e-4, np.abs(got[3] - ref[3]).max()
 
 
+def test_backward_full_size_training_config(attn):
+    """c2 at its full size (B4 H16, 16 frames x 336 tokens), the launch configuration bench.py times;
+    B is cut to one batch element for the oracle's sake (heads are independent), every element checked."""
+    c = wl.CONFIGS["c2_train"]
+    got, ref, _ = _run(attn, 1, c["H"], c["T"], c["kv_frames"], c["q_frames"], c["F"], c["seed"] + 31)
+    _check(got[0], ref[0], "c2 dq")
+    _check(got[1], ref[1], "c2 dk")
+    _check(got[2], ref[2], "c2 dv")
+    assert np.abs(got[3] - ref[3]).max() <= 2e-4
+
+
 def test_forward_lse_on_split_and_general_paths(attn):
     """The log-sum-exp also comes out of the key-split launches (combine kernel) and of the general
     (fp32) kernel."""
