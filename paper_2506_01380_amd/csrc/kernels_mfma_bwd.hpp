@@ -140,7 +140,7 @@ __device__ __forceinline__ bf16x8 pack8(const f32x16& a, int g) {
 // dq: a workgroup owns 256 query rows (4 wavefronts x 64), walks over the visible key tiles.
 //   S^T = K.Q^T, dP^T = V.dO^T (A = K / V rows from LDS, B = Q^T / dO^T in registers)
 //   dS^T = P^T o (dP^T - delta),  dQ^T += K^T.dS^T (A = K^T by transposing read, B = dS^T accumulators)
-__global__ void __launch_bounds__(256, 1)
+__global__ void __launch_bounds__(256, 2)
 attn_bwd_dq_bf16_d64(BwdParams p) {
     __shared__ SmemRing sm;
     const BwdItem wi = decode_bwd(p.BH, p.n_q_tiles);
@@ -217,9 +217,10 @@ attn_bwd_dq_bf16_d64(BwdParams p) {
         if (wave_active && j0 < kmax_wave) {
             const __bf16* ks_ = sm.k[slot];
             const __bf16* vs_ = sm.v[slot];
-            f32x16 s_acc[2][2], dp_acc[2][2];  // [kb][qt]
+            const bool need_mask = j0 + kBN > kmin_wave;  // tile crosses some row's bound
 #pragma unroll
-            for (int kb = 0; kb < 2; ++kb) {
+            for (int kb = 0; kb < 2; ++kb) {  // 32 keys at a time: keeps the live accumulators at half
+                f32x16 s_acc[2], dp_acc[2];   // [qt]
                 bf16x8 kf[4], vf[4];
 #pragma unroll
                 for (int ks = 0; ks < 4; ++ks) {
@@ -229,41 +230,34 @@ attn_bwd_dq_bf16_d64(BwdParams p) {
 #pragma unroll
                 for (int qt = 0; qt < 2; ++qt)
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) { s_acc[kb][qt][r] = 0.f; dp_acc[kb][qt][r] = 0.f; }
+                    for (int r = 0; r < 16; ++r) { s_acc[qt][r] = 0.f; dp_acc[qt][r] = 0.f; }
 #pragma unroll
                 for (int ks = 0; ks < 4; ++ks)
 #pragma unroll
                     for (int qt = 0; qt < 2; ++qt) {
-                        s_acc[kb][qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], qf[qt][ks], s_acc[kb][qt], 0, 0, 0);
-                        dp_acc[kb][qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[ks], gf[qt][ks], dp_acc[kb][qt], 0, 0, 0);
+                        s_acc[qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], qf[qt][ks], s_acc[qt], 0, 0, 0);
+                        dp_acc[qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[ks], gf[qt][ks], dp_acc[qt], 0, 0, 0);
                     }
-            }
-            if (j0 + kBN > kmin_wave) {  // tile crosses some row's bound
-#pragma unroll
-                for (int kb = 0; kb < 2; ++kb)
+                if (need_mask) {
 #pragma unroll
                     for (int qt = 0; qt < 2; ++qt)
 #pragma unroll
                         for (int r = 0; r < 16; ++r) {
                             const int key = j0 + 32 * kb + 8 * (r >> 2) + 4 * h + (r & 3);
-                            if (key >= kmax_lane[qt]) s_acc[kb][qt][r] = -INFINITY;
+                            if (key >= kmax_lane[qt]) s_acc[qt][r] = -INFINITY;
                         }
-            }
-            // dS^T = P^T o (dP^T - delta), written over the score accumulators
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
+                }
+                // dS^T = P^T o (dP^T - delta), written over the score accumulators
 #pragma unroll
                 for (int qt = 0; qt < 2; ++qt)
 #pragma unroll
                     for (int r = 0; r < 16; ++r) {
-                        const float pr = __builtin_amdgcn_exp2f(__builtin_fmaf(s_acc[kb][qt][r], c, -lse2[qt]));
-                        s_acc[kb][qt][r] = pr * (dp_acc[kb][qt][r] - dl[qt]);
+                        const float pr = __builtin_amdgcn_exp2f(__builtin_fmaf(s_acc[qt][r], c, -lse2[qt]));
+                        s_acc[qt][r] = pr * (dp_acc[qt][r] - dl[qt]);
                     }
 #pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
                 for (int g = 0; g < 2; ++g) {
-                    const bf16x8 ds0 = pack8(s_acc[kb][0], g), ds1 = pack8(s_acc[kb][1], g);
+                    const bf16x8 ds0 = pack8(s_acc[0], g), ds1 = pack8(s_acc[1], g);
 #pragma unroll
                     for (int dt = 0; dt < 2; ++dt) {
                         const bf16x8 kt = read_tr_frag(ks_, fo, kb, g, dt);
@@ -271,6 +265,7 @@ attn_bwd_dq_bf16_d64(BwdParams p) {
                         dq_acc[dt][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kt, ds1, dq_acc[dt][1], 0, 0, 0);
                     }
                 }
+            }
         }
         slot = slot == 2 ? 0 : slot + 1;
     }
@@ -388,6 +383,7 @@ attn_bwd_dkdv_bf16_d64(BwdParams p) {
             const __bf16* qs_ = sm.q[slot];
             const __bf16* gs_ = sm.g[slot];
             const bool need_mask = i0 < rmax_wave;
+            const bool ragged = i0 + 64 > p.Sq;
 #pragma unroll
             for (int qb = 0; qb < 2; ++qb) {  // 32 query rows at a time
                 f32x16 s_acc[2], dp_acc[2];   // [kt]
@@ -412,18 +408,24 @@ attn_bwd_dkdv_bf16_d64(BwdParams p) {
                 f32x4 lse4[4], dl4[4];
 #pragma unroll
                 for (int g4 = 0; g4 < 4; ++g4) {
-                    lse4[g4] = *(const f32x4*)(&sm.ld[slot][0][32 * qb + 8 * g4 + 4 * h]);
+                    lse4[g4] = *(const f32x4*)(&sm.ld[slot][0][32 * qb + 8 * g4 + 4 * h]) * kLog2e;
                     dl4[g4] = *(const f32x4*)(&sm.ld[slot][1][32 * qb + 8 * g4 + 4 * h]);
+                }
+                if (need_mask || ragged) {  // wave-uniform: rows the lane's key may not see, and the clamped
+                                            // duplicate rows of a ragged last tile
+#pragma unroll
+                    for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) {
+                            const int i = i0 + 32 * qb + 8 * (r >> 2) + 4 * h + (r & 3);
+                            if (i < rmin_lane[kt] || i >= p.Sq) s_acc[kt][r] = -INFINITY;
+                        }
                 }
 #pragma unroll
                 for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
                     for (int r = 0; r < 16; ++r) {
-                        const int i = i0 + 32 * qb + 8 * (r >> 2) + 4 * h + (r & 3);
-                        float s = s_acc[kt][r];
-                        if (need_mask && i < rmin_lane[kt]) s = -INFINITY;
-                        if (i >= p.Sq) s = -INFINITY;  // clamped duplicate rows of a ragged last tile
-                        const float pr = __builtin_amdgcn_exp2f(__builtin_fmaf(s, c, -lse4[r >> 2][r & 3] * kLog2e));
+                        const float pr = __builtin_amdgcn_exp2f(__builtin_fmaf(s_acc[kt][r], c, -lse4[r >> 2][r & 3]));
                         s_acc[kt][r] = pr;                                                // P
                         dp_acc[kt][r] = pr * (dp_acc[kt][r] - dl4[r >> 2][r & 3]);        // dS
                     }
