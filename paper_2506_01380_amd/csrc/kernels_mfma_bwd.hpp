@@ -35,7 +35,7 @@ struct BwdParams {
     void* dv;            // [BH, Scap, D], rows < Sk written
     int BH, Sq, Sk, Scap, T, P;
     int n_q_tiles;       // 256-row query tiles per head (dq kernel)
-    int n_k_blocks;      // 256-key blocks per head (dk/dv kernel)
+    int n_k_blocks;      // key blocks per head (dk/dv kernel)
     float scale;
     float scale_log2e;
 };
@@ -287,8 +287,8 @@ attn_bwd_dq_bf16_d64(BwdParams p) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// dk, dv: a workgroup owns 256 keys (4 wavefronts x 64), walks over the 64-row query tiles that
-// can see them (all rows from the first frame that sees the block's first key).
+// dk, dv: a workgroup owns 4 x 32 KT keys (KT = 1: 128 keys, two wavefronts per SIMD; KT = 2: 256 keys,
+// one wavefront per SIMD), walks over the 64-row query tiles that can see them (all rows from the first frame that sees the block's first key).
 //   S = Q.K^T, dP = dO.V^T (A = Q / dO rows from LDS, B = K^T / V^T in registers)
 //   dV^T += dO^T.P, dK^T += Q^T.dS (A by transposing reads of the dO / Q tile, B = P / dS accumulators)
 // In the accumulator layout a lane holds ONE key column and 16 of a block's 32 query rows, so the
@@ -301,8 +301,10 @@ struct __attribute__((aligned(16))) SmemBwdKv {
     float ld[3][4][64];  // per slot: [0] lse * log2e source values, [1] delta, [2], [3] padding loads
 };
 
-__global__ void __launch_bounds__(256, 1)
+template <int KT>
+__global__ void __launch_bounds__(256, KT == 1 ? 2 : 1)
 attn_bwd_dkdv_bf16_d64(BwdParams p) {
+    constexpr int KW = 32 * KT;  // keys per wavefront
     __shared__ SmemBwdKv sm;
     const BwdItem wi = decode_bwd(p.BH, p.n_k_blocks);
     if (!wi.valid) return;
@@ -311,8 +313,8 @@ attn_bwd_dkdv_bf16_d64(BwdParams p) {
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n = lane & 31, h = lane >> 5;
-    const int k0 = k_block * 256;
-    const int kw0 = k0 + wave * 64;
+    const int k0 = k_block * (4 * KW);
+    const int kw0 = k0 + wave * KW;
 
     const __bf16* qg = (const __bf16*)p.q + (int64_t)wi.bh * p.Sq * kD;
     const __bf16* gg = (const __bf16*)p.dout + (int64_t)wi.bh * p.Sq * kD;
@@ -322,10 +324,10 @@ attn_bwd_dkdv_bf16_d64(BwdParams p) {
     const float* dl_g = p.delta + (int64_t)wi.bh * p.Sq;
 
     // ---- this wavefront's keys: B operands K^T, V^T and the visibility bound of the lane's key ----
-    int key[2], rmin_lane[2];
-    bf16x8 kf[2][4], vf[2][4];
+    int key[KT], rmin_lane[KT];
+    bf16x8 kf[KT][4], vf[KT][4];
 #pragma unroll
-    for (int kt = 0; kt < 2; ++kt) {
+    for (int kt = 0; kt < KT; ++kt) {
         key[kt] = kw0 + 32 * kt + n;
         const int kc = min(key[kt], p.Sk - 1);  // ragged tail: a duplicate column, never stored
         rmin_lane[kt] = (kc / p.T - p.P) * p.T;  // <= 0: visible to every row
@@ -336,18 +338,18 @@ attn_bwd_dkdv_bf16_d64(BwdParams p) {
         }
     }
     const bool wave_active = kw0 < p.Sk;
-    const int kw_first = min(kw0, p.Sk - 1), kw_last = min(kw0 + 63, p.Sk - 1);
+    const int kw_first = min(kw0, p.Sk - 1), kw_last = min(kw0 + KW - 1, p.Sk - 1);
     const int rmin_wave = (kw_first / p.T - p.P) * p.T;  // tiles ending at or below it are skipped by this wavefront
     const int rmax_wave = (kw_last / p.T - p.P) * p.T;   // tiles starting at or above it need no mask
     const int rmin_wg = max(0, (k0 / p.T - p.P) * p.T);
     const int t_begin = rmin_wg / 64;
     const int t_end = (p.Sq + 63) / 64;
 
-    f32x16 dk_acc[2][2], dv_acc[2][2];  // [dt][kt]
+    f32x16 dk_acc[2][KT], dv_acc[2][KT];  // [dt][kt]
 #pragma unroll
     for (int a = 0; a < 2; ++a)
 #pragma unroll
-        for (int b = 0; b < 2; ++b)
+        for (int b = 0; b < KT; ++b)
 #pragma unroll
             for (int r = 0; r < 16; ++r) { dk_acc[a][b][r] = 0.f; dv_acc[a][b][r] = 0.f; }
     const float c = p.scale_log2e;
@@ -386,7 +388,7 @@ attn_bwd_dkdv_bf16_d64(BwdParams p) {
             const bool ragged = i0 + 64 > p.Sq;
 #pragma unroll
             for (int qb = 0; qb < 2; ++qb) {  // 32 query rows at a time
-                f32x16 s_acc[2], dp_acc[2];   // [kt]
+                f32x16 s_acc[KT], dp_acc[KT];   // [kt]
                 bf16x8 qa[4], ga[4];
 #pragma unroll
                 for (int ks = 0; ks < 4; ++ks) {
@@ -394,13 +396,13 @@ attn_bwd_dkdv_bf16_d64(BwdParams p) {
                     ga[ks] = lds_read_b128(gs_ + 32 * qb * kD + fo.row_frag[ks]);
                 }
 #pragma unroll
-                for (int kt = 0; kt < 2; ++kt)
+                for (int kt = 0; kt < KT; ++kt)
 #pragma unroll
                     for (int r = 0; r < 16; ++r) { s_acc[kt][r] = 0.f; dp_acc[kt][r] = 0.f; }
 #pragma unroll
                 for (int ks = 0; ks < 4; ++ks)
 #pragma unroll
-                    for (int kt = 0; kt < 2; ++kt) {
+                    for (int kt = 0; kt < KT; ++kt) {
                         s_acc[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa[ks], kf[kt][ks], s_acc[kt], 0, 0, 0);
                         dp_acc[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ga[ks], vf[kt][ks], dp_acc[kt], 0, 0, 0);
                     }
@@ -414,7 +416,7 @@ attn_bwd_dkdv_bf16_d64(BwdParams p) {
                 if (need_mask || ragged) {  // wave-uniform: rows the lane's key may not see, and the clamped
                                             // duplicate rows of a ragged last tile
 #pragma unroll
-                    for (int kt = 0; kt < 2; ++kt)
+                    for (int kt = 0; kt < KT; ++kt)
 #pragma unroll
                         for (int r = 0; r < 16; ++r) {
                             const int i = i0 + 32 * qb + 8 * (r >> 2) + 4 * h + (r & 3);
@@ -422,7 +424,7 @@ attn_bwd_dkdv_bf16_d64(BwdParams p) {
                         }
                 }
 #pragma unroll
-                for (int kt = 0; kt < 2; ++kt)
+                for (int kt = 0; kt < KT; ++kt)
 #pragma unroll
                     for (int r = 0; r < 16; ++r) {
                         const float pr = __builtin_amdgcn_exp2f(__builtin_fmaf(s_acc[kt][r], c, -lse4[r >> 2][r & 3]));
@@ -431,16 +433,18 @@ attn_bwd_dkdv_bf16_d64(BwdParams p) {
                     }
 #pragma unroll
                 for (int g = 0; g < 2; ++g) {
-                    const bf16x8 p0 = pack8(s_acc[0], g), p1 = pack8(s_acc[1], g);
-                    const bf16x8 d0 = pack8(dp_acc[0], g), d1 = pack8(dp_acc[1], g);
+                    bf16x8 pk[KT], dk_[KT];
+#pragma unroll
+                    for (int kt = 0; kt < KT; ++kt) { pk[kt] = pack8(s_acc[kt], g); dk_[kt] = pack8(dp_acc[kt], g); }
 #pragma unroll
                     for (int dt = 0; dt < 2; ++dt) {
                         const bf16x8 gt = read_tr_frag(gs_, fo, qb, g, dt);  // dO^T
                         const bf16x8 qt = read_tr_frag(qs_, fo, qb, g, dt);  // Q^T
-                        dv_acc[dt][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gt, p0, dv_acc[dt][0], 0, 0, 0);
-                        dv_acc[dt][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gt, p1, dv_acc[dt][1], 0, 0, 0);
-                        dk_acc[dt][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qt, d0, dk_acc[dt][0], 0, 0, 0);
-                        dk_acc[dt][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qt, d1, dk_acc[dt][1], 0, 0, 0);
+#pragma unroll
+                        for (int kt = 0; kt < KT; ++kt) {
+                            dv_acc[dt][kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gt, pk[kt], dv_acc[dt][kt], 0, 0, 0);
+                            dk_acc[dt][kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qt, dk_[kt], dk_acc[dt][kt], 0, 0, 0);
+                        }
                     }
                 }
             }
@@ -450,7 +454,7 @@ attn_bwd_dkdv_bf16_d64(BwdParams p) {
 
     if (!wave_active) return;
 #pragma unroll
-    for (int kt = 0; kt < 2; ++kt) {
+    for (int kt = 0; kt < KT; ++kt) {
         if (key[kt] >= p.Sk) continue;
         __bf16* dkg = (__bf16*)p.dk + ((int64_t)wi.bh * p.Scap + key[kt]) * kD;
         __bf16* dvg = (__bf16*)p.dv + ((int64_t)wi.bh * p.Scap + key[kt]) * kD;

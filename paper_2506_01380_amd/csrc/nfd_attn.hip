@@ -272,7 +272,8 @@ int nfd_block_causal_attn_bwd(nfd_attn_t* h, const void* q, const void* k, const
     p.dq = dq; p.dk = dk; p.dv = dv;
     p.BH = (int)BH; p.Sq = (int)Sq; p.Sk = (int)Sk; p.Scap = F * T; p.T = T; p.P = kv_frames - q_frames;
     p.n_q_tiles = (int)((Sq + nfd::mfma::kBM - 1) / nfd::mfma::kBM);
-    p.n_k_blocks = (int)((Sk + 255) / 256);
+    constexpr int kKeysPerWave = 32;  // 32: two wavefronts per SIMD; 64: one
+    p.n_k_blocks = (int)((Sk + 4 * kKeysPerWave - 1) / (4 * kKeysPerWave));
     p.scale = scale;
     p.scale_log2e = scale * nfd::kLog2e;
     hipStream_t st = (hipStream_t)stream;
@@ -280,7 +281,7 @@ int nfd_block_causal_attn_bwd(nfd_attn_t* h, const void* q, const void* k, const
     const unsigned heads8 = (unsigned)(8 * ((BH + 7) / 8));
     hipLaunchKernelGGL(nfd::mfma::attn_bwd_delta, dim3((unsigned)((rows * 8 + 255) / 256)), dim3(256), 0, st,
                        (const __bf16*)out, (const __bf16*)dout, p.delta, rows);
-    hipLaunchKernelGGL(nfd::mfma::attn_bwd_dkdv_bf16_d64, dim3(heads8 * p.n_k_blocks), dim3(256), 0, st, p);
+    hipLaunchKernelGGL(nfd::mfma::attn_bwd_dkdv_bf16_d64<kKeysPerWave / 32>, dim3(heads8 * p.n_k_blocks), dim3(256), 0, st, p);
     hipLaunchKernelGGL(nfd::mfma::attn_bwd_dq_bf16_d64, dim3(heads8 * p.n_q_tiles), dim3(256), 0, st, p);
     return check_hip(h, hipGetLastError(), "backward launch");
 }
