@@ -157,6 +157,60 @@ int nfd_rope_kvcache_append(nfd_attn_t* h, const void* q, void* q_out, void* k_c
 int nfd_rope_check_args(nfd_dtype_t dtype, int B, int H, int F, int T, int D, int frame_pos, int n_frames,
                         int grid_h, int grid_w, int n_t, int n_h, int n_w);
 
+/*
+ * Slide the context window (Sec. 5 "Limitations": the context is limited to a fixed number of frames):
+ * drop the oldest n_drop of the kv_frames cached frames of every head by moving frames
+ * [n_drop, kv_frames) to [0, kv_frames - n_drop).  k_cache, v_cache : [B, H, F*T, D].  Overlapping
+ * moves go through the handle's workspace when it is large enough, otherwise in runs of n_drop frames.
+ * The temporal positions of the remaining frames do not change: pass t_offset += n_drop to the next
+ * rotary-embedding call.  n_drop == 0 is a no-op.
+ * Errors: NFD_ERR_NULL, NFD_ERR_SHAPE (also n_drop > kv_frames), NFD_ERR_CAPACITY (kv_frames > F), NFD_ERR_HIP.
+ */
+int nfd_kvcache_shift(nfd_attn_t* h, void* k_cache, void* v_cache, int B, int H, int F, int T, int D,
+                      int kv_frames, int n_drop, void* stream);
+
+/*
+ * Bookkeeping of speculative sampling (Sec. 4.2 "Speculative Sampling"; Appendix A, "Detailed Algorithm of
+ * Speculative Sampling"): every model call generates n_spec frames under the CURRENT action repeated;
+ * afterwards the true actions of those frames are compared with it, the leading frames whose action
+ * matches are kept, the rest is discarded and generation resumes after the last verified frame.  Host
+ * only: no GPU, no HIP call, no allocation; the struct is plain data owned by the caller.
+ *
+ * Reading of the listing's `first_change_idx + 1`: the number of kept frames is the length of the run of
+ * the current action at the start of the chunk (at least 1: the first frame is generated under its own
+ * action).  Discarding needs no device work: the next call passes a smaller kv_frames and its append
+ * overwrites the rejected frames' K/V.
+ */
+typedef struct nfd_spec {
+    int capacity; /* F: frames the cache can hold */
+    int window;   /* frames of verified context kept; window + n_spec <= capacity */
+    int n_spec;   /* N: frames generated per model call */
+    int total;    /* frames of the whole video, prompt included */
+    int done;     /* frames verified so far, prompt included (the listing's i) */
+    int cached;   /* verified frames now in the cache */
+    int t_offset; /* absolute index of the frame in cache slot 0 */
+} nfd_spec_t;
+
+typedef struct nfd_spec_step {
+    int n_drop;    /* oldest frames to evict first: nfd_kvcache_shift(kv_frames = frame_pos + n_drop, n_drop) */
+    int frame_pos; /* cache frame where the new frames' K/V are appended */
+    int n_frames;  /* frames this call generates: min(n_spec, total - done) */
+    int kv_frames; /* arguments of the attention call: frame_pos + n_frames ... */
+    int q_frames;  /* ... and n_frames */
+    int t_offset;  /* temporal offset for the rotary embedding, after the eviction */
+} nfd_spec_step_t;
+
+/* n_prompt given frames are already in the cache.  Errors: NFD_ERR_NULL, NFD_ERR_SHAPE,
+ * NFD_ERR_CAPACITY (window + n_spec > capacity or n_prompt > capacity). */
+int nfd_spec_init(nfd_spec_t* s, int capacity, int window, int n_spec, int n_prompt, int total);
+/* Describe the next model call and apply its eviction to the bookkeeping.  Returns 1 if a call is
+ * due, 0 when all frames are done, < 0 on NULL. */
+int nfd_spec_next(nfd_spec_t* s, nfd_spec_step_t* step);
+/* After the call: actions is the host array [total, action_dim] of the true actions; *accepted
+ * receives the number of frames kept (1 .. step->n_frames).  Errors: NFD_ERR_NULL, NFD_ERR_SHAPE. */
+int nfd_spec_accept(nfd_spec_t* s, const nfd_spec_step_t* step, const int32_t* actions, int action_dim,
+                    int* accepted);
+
 /* Free the handle and its workspace.  NULL is accepted. */
 int nfd_attn_destroy(nfd_attn_t* h);
 

@@ -26,6 +26,7 @@ EXPORTS = (
     "nfd_last_error", "nfd_attn_check_args", "nfd_attn_plan", "nfd_attn_visible_pairs",
     "nfd_rope_kvcache_append", "nfd_rope_check_args",
     "nfd_block_causal_attn_fwd_lse", "nfd_block_causal_attn_bwd",
+    "nfd_kvcache_shift", "nfd_spec_init", "nfd_spec_next", "nfd_spec_accept",
 )
 
 
@@ -43,6 +44,17 @@ class Plan(ctypes.Structure):
         ("key_tiles_visited", ctypes.c_int64), ("key_tiles_dense", ctypes.c_int64),
         ("workspace_bytes", ctypes.c_size_t),
     ]
+
+    def as_dict(self):
+        return {n: getattr(self, n) for n, _ in self._fields_}
+
+
+class Spec(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int) for n in ("capacity", "window", "n_spec", "total", "done", "cached", "t_offset")]
+
+
+class SpecStep(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int) for n in ("n_drop", "frame_pos", "n_frames", "kv_frames", "q_frames", "t_offset")]
 
     def as_dict(self):
         return {n: getattr(self, n) for n, _ in self._fields_}
@@ -75,6 +87,15 @@ def lib():
         L.nfd_rope_kvcache_append.restype = ci
         L.nfd_rope_check_args.argtypes = [ci] * 13
         L.nfd_rope_check_args.restype = ci
+        L.nfd_kvcache_shift.argtypes = [vp, vp, vp] + [ci] * 7 + [vp]
+        L.nfd_kvcache_shift.restype = ci
+        L.nfd_spec_init.argtypes = [ctypes.POINTER(Spec)] + [ci] * 5
+        L.nfd_spec_init.restype = ci
+        L.nfd_spec_next.argtypes = [ctypes.POINTER(Spec), ctypes.POINTER(SpecStep)]
+        L.nfd_spec_next.restype = ci
+        L.nfd_spec_accept.argtypes = [ctypes.POINTER(Spec), ctypes.POINTER(SpecStep), ctypes.POINTER(ctypes.c_int32), ci,
+                                      ctypes.POINTER(ci)]
+        L.nfd_spec_accept.restype = ci
         L.nfd_attn_destroy.argtypes = [vp]
         L.nfd_attn_destroy.restype = ci
         L.nfd_last_error.argtypes = [vp]
@@ -156,6 +177,36 @@ def nfd_rope_kvcache_append(h, q, q_out, k_cache, v_cache, k_new, v_new, B, H, F
 
 def nfd_rope_check_args(dtype, B, H, F, T, D, frame_pos, n_frames, grid_h, grid_w, n_t, n_h, n_w):
     return lib().nfd_rope_check_args(dtype, B, H, F, T, D, frame_pos, n_frames, grid_h, grid_w, n_t, n_h, n_w)
+
+
+def nfd_kvcache_shift(h, k_cache, v_cache, B, H, F, T, D, kv_frames, n_drop, stream=None):
+    rc = lib().nfd_kvcache_shift(h, _addr(k_cache), _addr(v_cache), B, H, F, T, D, kv_frames, n_drop, _stream(stream))
+    _check(rc, "nfd_kvcache_shift", h)
+
+
+def nfd_spec_init(capacity, window, n_spec, n_prompt, total):
+    s = Spec()
+    _check(lib().nfd_spec_init(ctypes.byref(s), capacity, window, n_spec, n_prompt, total), "nfd_spec_init")
+    return s
+
+
+def nfd_spec_next(s):
+    """Returns the next step (SpecStep) or None when all frames are done."""
+    st = SpecStep()
+    rc = lib().nfd_spec_next(ctypes.byref(s), ctypes.byref(st))
+    if rc < 0:
+        _check(rc, "nfd_spec_next")
+    return st if rc == 1 else None
+
+
+def nfd_spec_accept(s, step, actions):
+    """actions: C-contiguous int32 numpy array [total, action_dim] on the host.  Returns the frames kept."""
+    import numpy as np
+    a = np.ascontiguousarray(actions, dtype=np.int32)
+    n = ctypes.c_int(0)
+    _check(lib().nfd_spec_accept(ctypes.byref(s), ctypes.byref(step), a.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)),
+                                 a.shape[1], ctypes.byref(n)), "nfd_spec_accept")
+    return n.value
 
 
 def nfd_attn_destroy(h):

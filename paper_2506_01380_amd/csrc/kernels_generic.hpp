@@ -87,34 +87,36 @@ attn_fwd_generic(FwdParams p) {
     if (p.lse && lane == 0) p.lse[row_id] = (m + log2f(l)) * kLn2;
 }
 
-// Copy n_frames frames of every head into the cache at frame_pos (Appendix B, KV caching).
-// One 16-byte vector per thread-iteration; row_vecs = T*D*sizeof(elem)/16 per frame.
+// Copy a run of whole frames of every head between two head-strided tensors: the cache write of new
+// frames (Appendix B, KV caching) and the moves of the sliding context window.  K and V together.
+// One 16-byte vector per thread-iteration; all counts in vectors: head_dst / head_src = head strides,
+// off_dst / off_src = offsets inside a head, len = vectors per head, total = heads * len.
 __global__ void __launch_bounds__(256)
-kvcache_append_vec16(u32x4* __restrict__ kc, u32x4* __restrict__ vc, const u32x4* __restrict__ kn,
-                     const u32x4* __restrict__ vn, int64_t head_vecs_cache, int64_t head_vecs_new,
-                     int64_t offset_vecs, int64_t total_vecs) {
-    for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total_vecs;
+kvcache_append_vec16(u32x4* __restrict__ kd, u32x4* __restrict__ vd, const u32x4* __restrict__ ks,
+                     const u32x4* __restrict__ vs, int64_t head_dst, int64_t head_src, int64_t off_dst,
+                     int64_t off_src, int64_t len, int64_t total) {
+    for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total;
          idx += (int64_t)gridDim.x * blockDim.x) {
-        const int64_t bh = idx / head_vecs_new, r = idx % head_vecs_new;
-        const int64_t dst = bh * head_vecs_cache + offset_vecs + r;
-        kc[dst] = kn[idx];
-        vc[dst] = vn[idx];
+        const int64_t bh = idx / len, r = idx % len;
+        const int64_t dst = bh * head_dst + off_dst + r, src = bh * head_src + off_src + r;
+        kd[dst] = ks[src];
+        vd[dst] = vs[src];
     }
 }
 // Element-granular variant for shapes whose frame size is not a multiple of 16 bytes.
 template <typename E>
 __global__ void __launch_bounds__(256)
-kvcache_append_elem(E* __restrict__ kc, E* __restrict__ vc, const E* __restrict__ kn, const E* __restrict__ vn,
-                    int64_t head_cache, int64_t head_new, int64_t offset, int64_t total) {
+kvcache_append_elem(E* __restrict__ kd, E* __restrict__ vd, const E* __restrict__ ks, const E* __restrict__ vs,
+                    int64_t head_dst, int64_t head_src, int64_t off_dst, int64_t off_src, int64_t len,
+                    int64_t total) {
     for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total;
          idx += (int64_t)gridDim.x * blockDim.x) {
-        const int64_t bh = idx / head_new, r = idx % head_new;
-        const int64_t dst = bh * head_cache + offset + r;
-        kc[dst] = kn[idx];
-        vc[dst] = vn[idx];
+        const int64_t bh = idx / len, r = idx % len;
+        const int64_t dst = bh * head_dst + off_dst + r, src = bh * head_src + off_src + r;
+        kd[dst] = ks[src];
+        vd[dst] = vs[src];
     }
 }
-
 
 // ---------------------------------------------------------------------------------------------
 // 3D rotary position embedding of the queries and keys of the new frames, fused with the cache

@@ -286,6 +286,34 @@ int nfd_block_causal_attn_bwd(nfd_attn_t* h, const void* q, const void* k, const
     return check_hip(h, hipGetLastError(), "backward launch");
 }
 
+// Launch one K+V frame-run copy (see kvcache_append_vec16); all arguments in elements.
+static void launch_frame_copy(nfd_attn_t* h, void* kd, void* vd, const void* ks, const void* vs, int64_t BH,
+                              int64_t head_dst, int64_t head_src, int64_t off_dst, int64_t off_src, int64_t len,
+                              hipStream_t st) {
+    const size_t es = elem_size(h->dtype);
+    const bool vec = (head_dst * es) % 16 == 0 && (head_src * es) % 16 == 0 && (off_dst * es) % 16 == 0 &&
+                     (off_src * es) % 16 == 0 && (len * es) % 16 == 0 && ((uintptr_t)kd % 16 == 0) &&
+                     ((uintptr_t)vd % 16 == 0) && ((uintptr_t)ks % 16 == 0) && ((uintptr_t)vs % 16 == 0);
+    if (vec) {
+        const int64_t f = 16 / es, total = BH * len / f;
+        const unsigned grid = (unsigned)std::min<int64_t>((total + 255) / 256, (int64_t)h->num_cus * 16);
+        hipLaunchKernelGGL(nfd::kvcache_append_vec16, dim3(grid), dim3(256), 0, st, (nfd::u32x4*)kd, (nfd::u32x4*)vd,
+                           (const nfd::u32x4*)ks, (const nfd::u32x4*)vs, head_dst / f, head_src / f, off_dst / f,
+                           off_src / f, len / f, total);
+    } else {
+        const int64_t total = BH * len;
+        const unsigned grid = (unsigned)std::min<int64_t>((total + 255) / 256, (int64_t)h->num_cus * 16);
+        if (es == 2)
+            hipLaunchKernelGGL(nfd::kvcache_append_elem<uint16_t>, dim3(grid), dim3(256), 0, st, (uint16_t*)kd,
+                               (uint16_t*)vd, (const uint16_t*)ks, (const uint16_t*)vs, head_dst, head_src, off_dst,
+                               off_src, len, total);
+        else
+            hipLaunchKernelGGL(nfd::kvcache_append_elem<uint32_t>, dim3(grid), dim3(256), 0, st, (uint32_t*)kd,
+                               (uint32_t*)vd, (const uint32_t*)ks, (const uint32_t*)vs, head_dst, head_src, off_dst,
+                               off_src, len, total);
+    }
+}
+
 int nfd_kvcache_append(nfd_attn_t* h, void* k_cache, void* v_cache, const void* k_new, const void* v_new, int B,
                        int H, int F, int T, int D, int frame_pos, int n_frames, void* stream) {
     if (!h) return NFD_ERR_NULL;
@@ -294,32 +322,87 @@ int nfd_kvcache_append(nfd_attn_t* h, void* k_cache, void* v_cache, const void* 
         return fail(h, NFD_ERR_SHAPE, "invalid shape arguments");
     if ((int64_t)frame_pos + n_frames > F) return fail(h, NFD_ERR_CAPACITY, "frame_pos + n_frames exceeds the cache capacity F");
     if (n_frames == 0) return NFD_OK;
-    const size_t es = elem_size(h->dtype);
     const int64_t frame_elems = (int64_t)T * D;
-    const int64_t BH = (int64_t)B * H;
-    hipStream_t st = (hipStream_t)stream;
-    const bool vec = (frame_elems * es) % 16 == 0 && ((uintptr_t)k_cache % 16 == 0) && ((uintptr_t)v_cache % 16 == 0) &&
-                     ((uintptr_t)k_new % 16 == 0) && ((uintptr_t)v_new % 16 == 0);
-    if (vec) {
-        const int64_t fv = frame_elems * es / 16;
-        const int64_t total = BH * n_frames * fv;
-        const unsigned grid = (unsigned)std::min<int64_t>((total + 255) / 256, (int64_t)h->num_cus * 16);
-        hipLaunchKernelGGL(nfd::kvcache_append_vec16, dim3(grid), dim3(256), 0, st, (nfd::u32x4*)k_cache,
-                           (nfd::u32x4*)v_cache, (const nfd::u32x4*)k_new, (const nfd::u32x4*)v_new, (int64_t)F * fv,
-                           (int64_t)n_frames * fv, (int64_t)frame_pos * fv, total);
-    } else {
-        const int64_t total = BH * n_frames * frame_elems;
-        const unsigned grid = (unsigned)std::min<int64_t>((total + 255) / 256, (int64_t)h->num_cus * 16);
-        if (es == 2)
-            hipLaunchKernelGGL(nfd::kvcache_append_elem<uint16_t>, dim3(grid), dim3(256), 0, st, (uint16_t*)k_cache,
-                               (uint16_t*)v_cache, (const uint16_t*)k_new, (const uint16_t*)v_new, (int64_t)F * frame_elems,
-                               (int64_t)n_frames * frame_elems, (int64_t)frame_pos * frame_elems, total);
-        else
-            hipLaunchKernelGGL(nfd::kvcache_append_elem<uint32_t>, dim3(grid), dim3(256), 0, st, (uint32_t*)k_cache,
-                               (uint32_t*)v_cache, (const uint32_t*)k_new, (const uint32_t*)v_new, (int64_t)F * frame_elems,
-                               (int64_t)n_frames * frame_elems, (int64_t)frame_pos * frame_elems, total);
-    }
+    launch_frame_copy(h, k_cache, v_cache, k_new, v_new, (int64_t)B * H, (int64_t)F * frame_elems,
+                      (int64_t)n_frames * frame_elems, (int64_t)frame_pos * frame_elems, 0,
+                      (int64_t)n_frames * frame_elems, (hipStream_t)stream);
     return check_hip(h, hipGetLastError(), "kvcache append launch");
+}
+
+int nfd_kvcache_shift(nfd_attn_t* h, void* k_cache, void* v_cache, int B, int H, int F, int T, int D,
+                      int kv_frames, int n_drop, void* stream) {
+    if (!h) return NFD_ERR_NULL;
+    if (!k_cache || !v_cache) return fail(h, NFD_ERR_NULL, "caches must be non-null");
+    if (B < 1 || H < 1 || F < 1 || T < 1 || D < 1 || kv_frames < 0 || n_drop < 0 || n_drop > kv_frames)
+        return fail(h, NFD_ERR_SHAPE, "invalid shape arguments");
+    if (kv_frames > F) return fail(h, NFD_ERR_CAPACITY, "kv_frames exceeds the cache capacity F");
+    const int keep = kv_frames - n_drop;
+    if (n_drop == 0 || keep == 0) return NFD_OK;
+    const int64_t fe = (int64_t)T * D, BH = (int64_t)B * H, head = (int64_t)F * fe;
+    const size_t es = elem_size(h->dtype);
+    hipStream_t st = (hipStream_t)stream;
+    const size_t half = ((size_t)(BH * keep * fe) * es + 255) / 256 * 256;  // staging bytes per tensor
+    if (keep <= n_drop) {
+        // source and destination frames are disjoint: one copy inside the caches
+        launch_frame_copy(h, k_cache, v_cache, k_cache, v_cache, BH, head, head, 0, (int64_t)n_drop * fe, keep * fe, st);
+    } else if (2 * half <= h->workspace_bytes) {
+        // overlapping ranges: through the workspace (out, then back)
+        void* ks = h->workspace;
+        void* vs = (char*)h->workspace + half;
+        launch_frame_copy(h, ks, vs, k_cache, v_cache, BH, keep * fe, head, 0, (int64_t)n_drop * fe, keep * fe, st);
+        launch_frame_copy(h, k_cache, v_cache, ks, vs, BH, head, keep * fe, 0, 0, keep * fe, st);
+    } else {
+        // workspace too small: runs of n_drop frames, oldest first; within a run source and destination are disjoint
+        for (int f = n_drop; f < kv_frames; f += n_drop) {
+            const int n = std::min(n_drop, kv_frames - f);
+            launch_frame_copy(h, k_cache, v_cache, k_cache, v_cache, BH, head, head, (int64_t)(f - n_drop) * fe,
+                              (int64_t)f * fe, (int64_t)n * fe, st);
+        }
+    }
+    return check_hip(h, hipGetLastError(), "kvcache shift launch");
+}
+
+// ---- speculative sampling bookkeeping (host only) ---------------------------------------------
+int nfd_spec_init(nfd_spec_t* s, int capacity, int window, int n_spec, int n_prompt, int total) {
+    if (!s) return NFD_ERR_NULL;
+    if (capacity < 1 || window < 1 || n_spec < 1 || n_prompt < 1 || total < n_prompt) return NFD_ERR_SHAPE;
+    if ((int64_t)window + n_spec > capacity || n_prompt > capacity) return NFD_ERR_CAPACITY;
+    s->capacity = capacity; s->window = window; s->n_spec = n_spec; s->total = total;
+    s->done = n_prompt; s->cached = n_prompt; s->t_offset = 0;
+    return NFD_OK;
+}
+
+int nfd_spec_next(nfd_spec_t* s, nfd_spec_step_t* step) {
+    if (!s || !step) return NFD_ERR_NULL;
+    if (s->done >= s->total) return 0;
+    step->n_drop = std::max(0, s->cached - s->window);  // keep at most `window` frames of context
+    s->cached -= step->n_drop;
+    s->t_offset += step->n_drop;
+    step->n_frames = std::min(s->n_spec, s->total - s->done);
+    step->frame_pos = s->cached;
+    step->kv_frames = s->cached + step->n_frames;
+    step->q_frames = step->n_frames;
+    step->t_offset = s->t_offset;
+    return 1;
+}
+
+int nfd_spec_accept(nfd_spec_t* s, const nfd_spec_step_t* step, const int32_t* actions, int action_dim,
+                    int* accepted) {
+    if (!s || !step || !actions || !accepted) return NFD_ERR_NULL;
+    if (action_dim < 1 || step->n_frames < 1 || s->done + step->n_frames > s->total) return NFD_ERR_SHAPE;
+    // frames were generated under the action of frame `done` repeated: keep the leading run that matches
+    const int32_t* a0 = actions + (int64_t)s->done * action_dim;
+    int n = 1;
+    for (; n < step->n_frames; ++n) {
+        const int32_t* an = actions + (int64_t)(s->done + n) * action_dim;
+        bool same = true;
+        for (int d = 0; d < action_dim; ++d) same = same && an[d] == a0[d];
+        if (!same) break;
+    }
+    *accepted = n;
+    s->done += n;
+    s->cached = step->frame_pos + n;  // the rejected frames' K/V are simply overwritten by the next append
+    return NFD_OK;
 }
 
 int nfd_rope_check_args(nfd_dtype_t dtype, int B, int H, int F, int T, int D, int frame_pos, int n_frames,

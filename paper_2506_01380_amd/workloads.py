@@ -30,6 +30,16 @@ CONFIGS = {
     "c5b_batch_decode": dict(B=8, H=16, D=64, T=576, kv_frames=64, q_frames=1,  F=64, dtype="bf16", seed=BASE_SEED + 15),
 }
 
+# The paper's other model sizes (Appendix, model-size table: 130M has 12 heads, 774M has 24, width 64)
+# and its third speculative chunk length (Tab. 2: N = 3).  Parity cases, not bench lines.
+EXTRA_CONFIGS = {
+    "x_train_h12":  dict(B=2, H=12, D=64, T=336, kv_frames=16, q_frames=16, F=16, dtype="bf16", seed=BASE_SEED + 31),
+    "x_train_h24":  dict(B=1, H=24, D=64, T=336, kv_frames=16, q_frames=16, F=16, dtype="bf16", seed=BASE_SEED + 32),
+    "x_decode_h12": dict(B=1, H=12, D=64, T=336, kv_frames=33, q_frames=1,  F=40, dtype="bf16", seed=BASE_SEED + 33),
+    "x_decode_h24": dict(B=1, H=24, D=64, T=336, kv_frames=33, q_frames=1,  F=40, dtype="bf16", seed=BASE_SEED + 34),
+    "x_spec_k3":    dict(B=1, H=16, D=64, T=336, kv_frames=35, q_frames=3,  F=40, dtype="bf16", seed=BASE_SEED + 35),
+}
+
 
 def round_to_bf16(x: np.ndarray) -> np.ndarray:
     """Round fp32 values to the nearest bf16 (ties to even); result stays fp32."""
@@ -64,7 +74,7 @@ def make_qkv(B, H, D, T, kv_frames, q_frames, F=None, dtype="bf16", seed=BASE_SE
 
 
 def make_config(name: str):
-    cfg = dict(CONFIGS[name])
+    cfg = dict(CONFIGS[name] if name in CONFIGS else EXTRA_CONFIGS[name])
     q, k, v = make_qkv(**cfg)
     return cfg, q, k, v
 

@@ -195,14 +195,15 @@ def test_future_frames_do_not_influence_past_rows_bitwise(attn_bf16):
 
 
 # ---- the paper-shaped configs at full size, on sampled rows -------------------------------------
-FULL = ["c2_train", "c3_decode", "c4_spec_k2", "c4_spec_k4", "c4_spec_k8", "c5a_long_train", "c5b_batch_decode"]
+FULL = ["c2_train", "c3_decode", "c4_spec_k2", "c4_spec_k4", "c4_spec_k8", "c5a_long_train", "c5b_batch_decode",
+        "x_train_h12", "x_train_h24", "x_decode_h12", "x_decode_h24", "x_spec_k3"]  # x_: other model sizes, N = 3
 
 
 @pytest.mark.parametrize("name", FULL)
 def test_full_size_configs_sampled_rows(attn_bf16, name):
     cfg, q, k, v = wl.make_config(name)
     T, kvf, qf = cfg["T"], cfg["kv_frames"], cfg["q_frames"]
-    per_frame = {"c2_train": 8, "c5a_long_train": 3, "c5b_batch_decode": 24}.get(name, 32)
+    per_frame = {"c2_train": 8, "c5a_long_train": 3, "c5b_batch_decode": 24, "x_train_h12": 8, "x_train_h24": 8}.get(name, 32)
     rows = wl.sample_rows(T, qf, per_frame, cfg["seed"])
     got = run_hip(attn_bf16, q, k, v, T, kvf, qf, "bf16")
     ref = orc.block_causal_attn(q, k, v, T, kv_frames=kvf, q_frames=qf, rows=rows)
