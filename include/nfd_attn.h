@@ -71,8 +71,8 @@ int nfd_attn_create(nfd_attn_t** h, nfd_dtype_t dtype, int device, size_t worksp
  * dtype of all four tensors is the handle's; bf16 computes on bf16 matrix cores
  * with fp32 accumulation and rounds the output to nearest-even; fp32 computes in fp32.
  * scale <= 0 selects 1/sqrt(D).  stream: a hipStream_t (NULL = default stream).
- * Supported: any B, H, T >= 1; D = 64 for bf16 on the matrix-core path, every other
- * D <= 256 and all fp32 shapes on the general path.  The device current on the calling
+ * Supported: any B, H, T >= 1; D = 64 for bf16 on the matrix-core path (q, k, v, out 16-byte
+ * aligned there), every other D <= 256 and all fp32 shapes on the general path.  The device current on the calling
  * thread must be the handle's device.
  * Ownership: the caller owns all four tensors; the library keeps no reference.
  * Errors (checked before any launch, in this order): NFD_ERR_NULL, NFD_ERR_SHAPE,
@@ -101,7 +101,8 @@ int nfd_block_causal_attn_fwd_lse(nfd_attn_t* h, const void* q, const void* k, c
  * out and lse are the results of nfd_block_causal_attn_fwd_lse on the same q, k, v, scale.  Of dk and
  * dv only the first kv_frames*T rows of every head are written.  No atomics: results are
  * bit-reproducible.  Uses the handle's workspace (4 bytes per query row).
- * Supported: bf16, D = 64 (any B, H, T, frames); everything else NFD_ERR_UNSUPPORTED.
+ * Supported: bf16, D = 64 (any B, H, T, frames), tensors 16-byte aligned; everything else
+ * NFD_ERR_UNSUPPORTED.
  * Errors, in this order: NFD_ERR_NULL, NFD_ERR_SHAPE, NFD_ERR_CAPACITY, NFD_ERR_UNSUPPORTED,
  * NFD_ERR_ALLOC (workspace too small), NFD_ERR_HIP.
  */

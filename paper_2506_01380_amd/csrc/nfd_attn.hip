@@ -195,6 +195,9 @@ static int fwd_impl(nfd_attn_t* h, const void* q, const void* k, const void* v, 
     // The plan is made against this handle's workspace; a schedule that would write partials past it
     // must never reach the device.
     if (pl.workspace_bytes > h->workspace_bytes) return fail(h, NFD_ERR_ALLOC, "key-split partials exceed the workspace");
+    // The matrix-core kernels move 16-byte vectors; a view that starts in the middle of a vector would fault.
+    if (pl.kernel == 1 && (((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)out) % 16 != 0 || (uintptr_t)lse % 4 != 0))
+        return fail(h, NFD_ERR_UNSUPPORTED, "q, k, v, out must be 16-byte aligned (lse 4-byte)");
     if (!(scale > 0.f)) scale = 1.0f / std::sqrt((float)D);
 
     nfd::FwdParams p{};
@@ -262,6 +265,9 @@ int nfd_block_causal_attn_bwd(nfd_attn_t* h, const void* q, const void* k, const
     if (h->dtype != NFD_BF16 || D != nfd::mfma::kD)
         return fail(h, NFD_ERR_UNSUPPORTED, "the backward is built for bf16 and head width 64");
     const int64_t BH = (int64_t)B * H, Sq = (int64_t)q_frames * T, Sk = (int64_t)kv_frames * T;
+    if (((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)out | (uintptr_t)dout | (uintptr_t)dq | (uintptr_t)dk |
+         (uintptr_t)dv) % 16 != 0 || (uintptr_t)lse % 4 != 0)
+        return fail(h, NFD_ERR_UNSUPPORTED, "tensors must be 16-byte aligned (lse 4-byte)");
     if ((size_t)(BH * Sq) * sizeof(float) > h->workspace_bytes)
         return fail(h, NFD_ERR_ALLOC, "the per-row workspace of the backward exceeds the handle's workspace");
     if (!(scale > 0.f)) scale = 1.0f / std::sqrt((float)D);

@@ -288,6 +288,18 @@ def test_error_codes_on_device(attn_bf16):
     assert e.value.code == nb.NFD_ERR_SHAPE
 
 
+def test_misaligned_views_are_refused_not_faulted(attn_bf16):
+    """A bf16 view that starts 2 bytes into a 16-byte vector must come back as an error code."""
+    B, H, T, D, F = 1, 1, 16, 64, 2
+    buf = torch.zeros(B * H * F * T * D + 8, dtype=torch.bfloat16, device="cuda")
+    q = buf[1:1 + B * H * F * T * D].view(B, H, F * T, D)
+    ok = buf[:B * H * F * T * D].view(B, H, F * T, D)
+    assert q.data_ptr() % 16 != 0
+    with pytest.raises(nb.NfdError) as e:
+        nb.nfd_block_causal_attn_fwd(attn_bf16.h, q, ok, ok, torch.empty_like(ok), B, H, F, T, D, F, F)
+    assert e.value.code == nb.NFD_ERR_UNSUPPORTED
+
+
 def test_runs_are_bit_reproducible(attn_bf16):
     cfg, q, k, v = wl.make_config("c4_spec_k2")
     a = run_hip(attn_bf16, q, k, v, cfg["T"], cfg["kv_frames"], cfg["q_frames"], "bf16")

@@ -95,3 +95,10 @@ def test_create_without_gpu_reports_an_error_code():
     with pytest.raises(nb.NfdError) as e:
         nb.nfd_attn_create(nb.NFD_BF16, 0)
     assert e.value.code in (nb.NFD_ERR_HIP, nb.NFD_ERR_ALLOC)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode != 0 and "one GPU" in r.stderr and r.stdout.strip() == ""
