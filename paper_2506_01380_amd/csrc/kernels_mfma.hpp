@@ -198,23 +198,6 @@ attn_fwd_bf16_d64(FwdParams p) {
     float m_used[2] = {kNegBig, kNegBig};  // reference max, raw score units (stale by design)
     float l_sum[2] = {0.f, 0.f};           // this lane's share of the row sum
     const float c = p.scale_log2e;
-#ifdef NFD_STAGE_TIMING
-    // development build: per-tile time stamps of the first 32 tiles of every wavefront
-    constexpr int kTraceTiles = 32;
-    unsigned* trace = p.timing ? (unsigned*)p.timing + ((size_t)blockIdx.x * 4 + wave) * (kTraceTiles * 4 + 4) : nullptr;
-    if (trace && lane == 0) {
-        unsigned hwid;
-        asm volatile("s_getreg_b32 %0, hwreg(HW_REG_HW_ID)" : "=s"(hwid));
-        unsigned xcc;
-        asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc));
-        trace[kTraceTiles * 4] = hwid;
-        trace[kTraceTiles * 4 + 1] = xcc;
-        trace[kTraceTiles * 4 + 2] = (unsigned)(t_end - t_begin);
-    }
-#define NFD_STAMP(k) if (trace && lane == 0 && t - t_begin < kTraceTiles) trace[(t - t_begin) * 4 + (k)] = (unsigned)__builtin_readcyclecounter();
-#else
-#define NFD_STAMP(k)
-#endif
 
     // ---- tile loads: one wave instruction fills 8 consecutive tile rows (1 KB); a wavefront owns
     // rows 8*wave + 32*pass + lane/8, and each lane fetches the chunk that belongs at its position ----
@@ -261,7 +244,6 @@ attn_fwd_bf16_d64(FwdParams p) {
 
     auto compute_tile = [&](int t, int slot) {
         const int j0 = t * kBN;
-        NFD_STAMP(0)
         if (wave_active && j0 < kmax_wave) {
             const __bf16* ks_ = sm.k[slot];
             const __bf16* vs_ = sm.v[slot];
@@ -292,10 +274,6 @@ attn_fwd_bf16_d64(FwdParams p) {
             }
             __builtin_amdgcn_sched_barrier(0);
             __builtin_amdgcn_s_setprio(0);
-#ifdef NFD_STAGE_TIMING
-            asm volatile("v_mov_b32 %0, %0" : "+v"(s_acc[1][1][15]));  // issues only once the scores are complete
-            NFD_STAMP(1)
-#endif
             bf16x8 vf[2][2][2];  // [kb][g][dt]
             auto read_v_frags = [&]() {
 #pragma unroll
@@ -387,7 +365,6 @@ attn_fwd_bf16_d64(FwdParams p) {
             l_sum[1] += l_tile[1];
             // ---- O^T += V^T . P^T -----------------------------------------------------------------
             __builtin_amdgcn_sched_barrier(0);
-            NFD_STAMP(2)
             __builtin_amdgcn_s_setprio(PRIO);
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb)
@@ -399,7 +376,6 @@ attn_fwd_bf16_d64(FwdParams p) {
                         for (int qt = 0; qt < 2; ++qt)
                             o_acc[dt][qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[kb][g][dt], pf[kb][g][qt], o_acc[dt][qt], 0, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
-            NFD_STAMP(3)
         }
     };
 

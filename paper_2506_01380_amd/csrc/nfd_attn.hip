@@ -219,12 +219,6 @@ static int fwd_impl(nfd_attn_t* h, const void* q, const void* k, const void* v, 
         p.part_o = (float*)h->workspace;
         p.part_ml = p.part_o + (size_t)p.BH * pl.n_splits * p.Sq * nfd::mfma::kD;
     }
-#ifdef NFD_STAGE_TIMING
-    {
-        const char* e = getenv("NFD_TIMING_BUF");
-        p.timing = e ? (unsigned long long*)strtoull(e, nullptr, 0) : nullptr;
-    }
-#endif
     hipStream_t st = (hipStream_t)stream;
 
     if (pl.kernel == 1) {

@@ -42,9 +42,6 @@ struct FwdParams {
     int n_splits;       // key splits per query tile
     int group_q_tiles;  // split launches: 1 = query tiles of one (head, split) get adjacent workgroup ids
     float scale_log2e;  // softmax scale * log2(e)
-#ifdef NFD_STAGE_TIMING
-    unsigned long long* timing;  // development builds only: per-wavefront stage cycle sums
-#endif
 };
 
 __device__ __forceinline__ int kmax_of_row(int row, int T, int P) { return (P + row / T + 1) * T; }
