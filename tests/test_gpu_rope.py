@@ -68,6 +68,8 @@ CASES = [
     ("fp32", 1, 2, (4, 4), 64, (16, 24, 24), 2, 4, 2, 100, 10000.0),      # fp32, large temporal positions
     ("fp32", 1, 1, (3, 5), 10, (2, 4, 4), 1, 2, 1, 0, 50.0),              # fp32 pair-wide path
     ("bf16", 1, 2, (2, 2), 64, (64, 0, 0), 2, 4, 1, 0, 10000.0),          # one axis only (textbook 1-D RoPE)
+    ("bf16", 1, 1, (3, 2), 256, (64, 96, 96), 1, 2, 1, 5, 10000.0),       # widest supported head (128 pairs)
+    ("bf16", 3, 7, (24, 24), 64, (16, 24, 24), 1, 3, 2, 61, 10000.0),     # T = 576, several heads per thread
 ]
 
 
