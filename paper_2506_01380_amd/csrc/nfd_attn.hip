@@ -1,6 +1,7 @@
 // Host side of the C ABI declared in include/nfd_attn.h: argument checks, tile schedule,
-// kernel selection and launches.  No allocation and no host synchronisation happens in
-// the forward or append calls.
+// kernel selection and launches.  Only nfd_attn_create / nfd_attn_destroy allocate or free;
+// no other call allocates, synchronises with the host or issues a memset, so all of them can
+// be captured into a HIP graph.
 #include "../../include/nfd_attn.h"
 
 #include <hip/hip_runtime.h>
