@@ -288,6 +288,21 @@ def test_error_codes_on_device(attn_bf16):
     assert e.value.code == nb.NFD_ERR_SHAPE
 
 
+def test_empty_appends_are_no_ops(attn_bf16):
+    """n_frames == 0: nothing is launched, nothing changes - for the plain and the rotary append."""
+    B, H, T, D, F = 1, 2, 16, 64, 3
+    kc = torch.randn(B, H, F * T, D, device="cuda").to(torch.bfloat16)
+    vc = torch.randn(B, H, F * T, D, device="cuda").to(torch.bfloat16)
+    k0, v0 = kc.clone(), vc.clone()
+    empty = torch.empty(B, H, 0, D, device="cuda", dtype=torch.bfloat16)
+    dummy = torch.zeros(8, device="cuda", dtype=torch.bfloat16)  # a valid pointer for the zero-row tensors
+    nb.nfd_kvcache_append(attn_bf16.h, kc, vc, dummy, dummy, B, H, F, T, D, 1, 0)
+    nb.nfd_rope_kvcache_append(attn_bf16.h, dummy, dummy, kc, vc, dummy, dummy, B, H, F, T, D, 3, 0, 0, 4, 4, 16, 24, 24)
+    nb.nfd_kvcache_shift(attn_bf16.h, kc, vc, B, H, F, T, D, 0, 0)
+    torch.cuda.synchronize()
+    assert torch.equal(kc, k0) and torch.equal(vc, v0) and empty.numel() == 0
+
+
 def test_misaligned_views_are_refused_not_faulted(attn_bf16):
     """A bf16 view that starts 2 bytes into a 16-byte vector must come back as an error code."""
     B, H, T, D, F = 1, 1, 16, 64, 2
