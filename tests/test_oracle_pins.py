@@ -267,3 +267,17 @@ def test_kvcache_append_places_frames():
     assert np.array_equal(got, want)
     with pytest.raises(ValueError):
         orc.kvcache_append(cache, fresh, T=T, frame_pos=4)
+
+
+def test_paper_stated_cost_reduction_fixture():
+    """tests/golden/cost_reduction.txt holds the paper's statement (Sec. 3.1) that the mask halves the cost:
+    the oracle's enumerated visible fraction of the training form agrees with it within the stated slack."""
+    import os
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "cost_reduction.txt")
+    rows = [l.split() for l in open(path) if l.strip() and not l.startswith("#")]
+    assert len(rows) >= 2
+    for frames, claim, slack in rows:
+        F, T = int(frames), 3
+        frac = orc.visible_pairs(T, F, F) / float((F * T) ** 2)
+        assert abs(frac - float(claim)) <= float(slack), (F, frac)
+        assert abs(frac - (F + 1) / (2.0 * F)) < 1e-12
