@@ -55,7 +55,7 @@ def main():
     attn = nb.Attention("bf16")
 
     def time_workload(name, steps, warmup, rotate=1):
-        cfg = wl.CONFIGS[name]
+        cfg = wl.CONFIGS[name] if name in wl.CONFIGS else wl.EXTRA_CONFIGS[name]
         B, H, D, T, kvf, qf, F = (cfg[x] for x in ("B", "H", "D", "T", "kv_frames", "q_frames", "F"))
         gen = torch.Generator(device="cuda").manual_seed(cfg["seed"])
         mk = lambda *s: torch.randn(*s, device="cuda", generator=gen, dtype=torch.float32).to(torch.bfloat16)

@@ -71,9 +71,11 @@ struct __attribute__((aligned(16))) SmemRing {
     __bf16 v[kRingSlots][kTileElems];
 };
 
-// Work decomposition of one launch.  Workgroup ids are dealt round-robin to the 8 XCDs;
-// heads are pinned to an XCD (bh % 8) so that all query tiles and key splits of a head
-// share one L2.  Inside an XCD:
+// Work decomposition of one launch.  Workgroup ids are dealt round-robin to the 8 XCDs.
+// When the head count is a multiple of 8, heads are pinned to an XCD (bh % 8) so that all query
+// tiles and key splits of a head share one L2; otherwise pinning would leave XCDs unevenly loaded
+// (or idle), and the items are dealt out plainly, consecutive ids going to consecutive heads.
+// Order of the items of an XCD (or of the launch):
 //  * by default the heaviest query tiles (latest frames) come first, heads fastest, so the tail
 //    of the launch is made of the lightest tiles;
 //  * group_q_tiles (key-split launches whose K/V exceed the last-level cache): the query tiles of
@@ -86,10 +88,11 @@ struct WorkItem {
 __device__ __forceinline__ WorkItem decode_work(const FwdParams& p) {
     WorkItem w;
     const int per_head = p.n_q_tiles * p.n_splits;
-    const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
-    const int heads_here = p.BH / 8 + (xcd < (p.BH & 7) ? 1 : 0);
-    w.valid = heads_here > 0 && j < heads_here * per_head;
-    const int hh = max(heads_here, 1);
+    const bool pinned = (p.BH & 7) == 0;
+    const int xcd = pinned ? (int)(blockIdx.x & 7) : 0;
+    const int j = pinned ? (int)(blockIdx.x >> 3) : (int)blockIdx.x;
+    const int hh = pinned ? p.BH >> 3 : p.BH;  // heads this id stream runs over
+    w.valid = j < hh * per_head;
     int head_local;
     if (!p.group_q_tiles) {
         const int item = j / hh;
@@ -102,7 +105,7 @@ __device__ __forceinline__ WorkItem decode_work(const FwdParams& p) {
         head_local = rest % hh;
         w.split = rest / hh;
     }
-    w.bh = head_local * 8 + xcd;
+    w.bh = pinned ? head_local * 8 + xcd : head_local;
     return w;
 }
 

@@ -59,19 +59,21 @@ attn_bwd_delta(const __bf16* __restrict__ out, const __bf16* __restrict__ dout, 
     if (row < rows && (idx & 7) == 0) delta[row] = s;
 }
 
-// Workgroup id -> (head, item): ids are dealt round-robin to the 8 XCDs, heads are pinned to an XCD
-// (bh % 8), and inside an XCD item 0 of every head comes first, then item 1, ...
+// Workgroup id -> (head, item): ids are dealt round-robin to the 8 XCDs; when the head count is a
+// multiple of 8 heads are pinned to an XCD (bh % 8), otherwise ids run plainly over the heads; either
+// way item 0 of every head comes first, then item 1, ...
 struct BwdItem {
     int bh, item;
     bool valid;
 };
 __device__ __forceinline__ BwdItem decode_bwd(int BH, int n_items) {
     BwdItem w;
-    const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
-    const int heads_here = BH / 8 + (xcd < (BH & 7) ? 1 : 0);
-    w.valid = heads_here > 0 && j < heads_here * n_items;
-    const int hh = max(heads_here, 1);
-    w.bh = (j % hh) * 8 + xcd;
+    const bool pinned = (BH & 7) == 0;
+    const int xcd = pinned ? (int)(blockIdx.x & 7) : 0;
+    const int j = pinned ? (int)(blockIdx.x >> 3) : (int)blockIdx.x;
+    const int hh = pinned ? BH >> 3 : BH;
+    w.valid = j < hh * n_items;
+    w.bh = pinned ? (j % hh) * 8 + xcd : j % hh;
     w.item = j / hh;
     return w;
 }

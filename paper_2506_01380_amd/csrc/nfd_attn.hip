@@ -119,7 +119,7 @@ int nfd_attn_plan(nfd_dtype_t dtype, int B, int H, int F, int T, int D, int kv_f
         }
 #endif
         pl.n_splits = splits;
-        pl.n_workgroups = (int)(8 * ((BH + 7) / 8) * pl.n_q_tiles * splits);
+        pl.n_workgroups = (int)(BH * pl.n_q_tiles * splits);
         pl.key_tiles_visited = visited * BH;
         pl.key_tiles_dense = (int64_t)pl.n_q_tiles * (((int64_t)kv_frames * T + pl.block_n - 1) / pl.block_n) * BH;
         pl.workspace_bytes = splits > 1 ? (size_t)(BH * Sq) * splits * (nfd::mfma::kD + 2) * sizeof(float) : 0;
@@ -279,7 +279,7 @@ int nfd_block_causal_attn_bwd(nfd_attn_t* h, const void* q, const void* k, const
     p.scale_log2e = scale * nfd::kLog2e;
     hipStream_t st = (hipStream_t)stream;
     const int64_t rows = BH * Sq;
-    const unsigned heads8 = (unsigned)(8 * ((BH + 7) / 8));
+    const unsigned heads8 = (unsigned)BH;  // one workgroup per (head, item)
     hipLaunchKernelGGL(nfd::mfma::attn_bwd_delta, dim3((unsigned)((rows * 8 + 255) / 256)), dim3(256), 0, st,
                        (const __bf16*)out, (const __bf16*)dout, p.delta, rows);
     hipLaunchKernelGGL(nfd::mfma::attn_bwd_dkdv_bf16_d64<kKeysPerWave / 32>, dim3(heads8 * p.n_k_blocks), dim3(256), 0, st, p);
