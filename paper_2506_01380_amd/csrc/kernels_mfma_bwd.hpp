@@ -7,7 +7,7 @@
 // Three launches, no atomics, bit-reproducible:
 //   attn_bwd_delta         delta_i = <do_i, o_i>                                   (streaming)
 //   attn_bwd_dq_bf16_d64   query-major, same decomposition and tile ring as the forward kernel
-//   attn_bwd_dkdv_bf16_d64 key-major: a wavefront owns 64 keys and walks over the query tiles that see them
+//   attn_bwd_dkdv_bf16_d64 key-major: a wavefront owns 32 (or 64) keys and walks over the query tiles that see them
 // Both matrix kernels recompute the weights from the stored log-sum-exp, so no online softmax is
 // needed, and both keep the operand whose rows they own in registers for the whole kernel.  Tiles
 // of the other operand go global -> LDS directly into the same XOR-swizzled ring as in the forward
@@ -15,8 +15,9 @@
 // operand unchanged (the contraction index is permuted identically on the A side by the transposing
 // LDS read), so neither P nor dS ever touches LDS.
 //
-// Register budget: these kernels hold two more accumulator sets than the forward one and are built
-// for one wavefront per SIMD (up to 512 registers); they are the first, untuned version.
+// Register budget: both kernels run two wavefronts per SIMD - the dq kernel by forming the scores of
+// 32 keys at a time, the dk/dv kernel by owning 32 keys per wavefront.  S and dP are formed in both
+// kernels (seven products for the five of the mathematics): the price of having no atomics on dq.
 #pragma once
 #include "kernels_mfma.hpp"
 
