@@ -205,7 +205,7 @@ def main():
 
     backward = None
     if args.bwd:
-        backward = time_bwd(args.workload, max(5, args.steps // 4), max(2, args.warmup // 4))
+        backward = time_bwd(args.workload, max(10, args.steps // 2), args.warmup)
         print(json.dumps(backward), file=sys.stderr, flush=True)
 
     pre_op = None
