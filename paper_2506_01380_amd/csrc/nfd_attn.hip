@@ -119,6 +119,7 @@ int nfd_attn_plan(nfd_dtype_t dtype, int B, int H, int F, int T, int D, int kv_f
         }
 #endif
         pl.n_splits = splits;
+        if (BH * pl.n_q_tiles * splits > (int64_t)0x7fffffff) return NFD_ERR_UNSUPPORTED;  // grid size
         pl.n_workgroups = (int)(BH * pl.n_q_tiles * splits);
         pl.key_tiles_visited = visited * BH;
         pl.key_tiles_dense = (int64_t)pl.n_q_tiles * (((int64_t)kv_frames * T + pl.block_n - 1) / pl.block_n) * BH;
@@ -129,6 +130,7 @@ int nfd_attn_plan(nfd_dtype_t dtype, int B, int H, int F, int T, int D, int kv_f
         pl.block_n = 64;
         pl.n_q_tiles = (int)((Sq + pl.block_m - 1) / pl.block_m);
         pl.n_splits = 1;
+        if ((BH * Sq + nfd::kGenericWaves - 1) / nfd::kGenericWaves > (int64_t)0x7fffffff) return NFD_ERR_UNSUPPORTED;
         pl.n_workgroups = (int)((BH * Sq + nfd::kGenericWaves - 1) / nfd::kGenericWaves);
         int64_t visited = 0;
         for (int64_t i = 0; i < Sq; ++i) visited += (kmax_rows(i, T, P) + 63) / 64;

@@ -102,3 +102,10 @@ def test_bench_refuses_more_than_one_gpu():
     import sys
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
     assert r.returncode != 0 and "one GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_plan_refuses_a_launch_beyond_the_grid_limit():
+    # 2^24 heads x 2^22 query tiles would overflow the workgroup count
+    rc = nb.lib().nfd_attn_plan(nb.NFD_BF16, 1 << 12, 1 << 12, 1 << 14, 1 << 16, 64, 1 << 14, 1 << 14, 0, 0,
+                                __import__("ctypes").byref(nb.Plan()))
+    assert rc == nb.NFD_ERR_UNSUPPORTED
