@@ -89,32 +89,20 @@ attn_fwd_generic(FwdParams p) {
 
 // Copy a run of whole frames of every head between two head-strided tensors: the cache write of new
 // frames (Appendix B, KV caching) and the moves of the sliding context window.  K and V together.
-// One 16-byte vector per thread-iteration; all counts in vectors: head_dst / head_src = head strides,
-// off_dst / off_src = offsets inside a head, len = vectors per head, total = heads * len.
-__global__ void __launch_bounds__(256)
-kvcache_append_vec16(u32x4* __restrict__ kd, u32x4* __restrict__ vd, const u32x4* __restrict__ ks,
-                     const u32x4* __restrict__ vs, int64_t head_dst, int64_t head_src, int64_t off_dst,
-                     int64_t off_src, int64_t len, int64_t total) {
-    for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total;
-         idx += (int64_t)gridDim.x * blockDim.x) {
-        const int64_t bh = idx / len, r = idx % len;
-        const int64_t dst = bh * head_dst + off_dst + r, src = bh * head_src + off_src + r;
-        kd[dst] = ks[src];
-        vd[dst] = vs[src];
-    }
-}
-// Element-granular variant for shapes whose frame size is not a multiple of 16 bytes.
+// All counts in units of the element type E (a 16-byte vector when every size and address allows it,
+// otherwise one tensor element): head_dst / head_src = head strides, off_dst / off_src = offsets
+// inside a head, len = units per head.  blockIdx.y walks over the heads, blockIdx.x over the units of a
+// head, so no thread divides.
 template <typename E>
 __global__ void __launch_bounds__(256)
-kvcache_append_elem(E* __restrict__ kd, E* __restrict__ vd, const E* __restrict__ ks, const E* __restrict__ vs,
-                    int64_t head_dst, int64_t head_src, int64_t off_dst, int64_t off_src, int64_t len,
-                    int64_t total) {
-    for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total;
-         idx += (int64_t)gridDim.x * blockDim.x) {
-        const int64_t bh = idx / len, r = idx % len;
-        const int64_t dst = bh * head_dst + off_dst + r, src = bh * head_src + off_src + r;
-        kd[dst] = ks[src];
-        vd[dst] = vs[src];
+kvcache_copy(E* __restrict__ kd, E* __restrict__ vd, const E* __restrict__ ks, const E* __restrict__ vs,
+             int64_t head_dst, int64_t head_src, int64_t off_dst, int64_t off_src, int64_t len, int64_t heads) {
+    for (int64_t bh = blockIdx.y; bh < heads; bh += gridDim.y) {
+        const int64_t dbase = bh * head_dst + off_dst, sbase = bh * head_src + off_src;
+        for (int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; r < len; r += (int64_t)gridDim.x * blockDim.x) {
+            kd[dbase + r] = ks[sbase + r];
+            vd[dbase + r] = vs[sbase + r];
+        }
     }
 }
 

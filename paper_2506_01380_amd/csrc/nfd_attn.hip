@@ -289,7 +289,7 @@ int nfd_block_causal_attn_bwd(nfd_attn_t* h, const void* q, const void* k, const
     return check_hip(h, hipGetLastError(), "backward launch");
 }
 
-// Launch one K+V frame-run copy (see kvcache_append_vec16); all arguments in elements.
+// Launch one K+V frame-run copy (see kvcache_copy); all arguments in elements.
 static void launch_frame_copy(nfd_attn_t* h, void* kd, void* vd, const void* ks, const void* vs, int64_t BH,
                               int64_t head_dst, int64_t head_src, int64_t off_dst, int64_t off_src, int64_t len,
                               hipStream_t st) {
@@ -297,23 +297,23 @@ static void launch_frame_copy(nfd_attn_t* h, void* kd, void* vd, const void* ks,
     const bool vec = (head_dst * es) % 16 == 0 && (head_src * es) % 16 == 0 && (off_dst * es) % 16 == 0 &&
                      (off_src * es) % 16 == 0 && (len * es) % 16 == 0 && ((uintptr_t)kd % 16 == 0) &&
                      ((uintptr_t)vd % 16 == 0) && ((uintptr_t)ks % 16 == 0) && ((uintptr_t)vs % 16 == 0);
+    const dim3 block(256);
+    auto grid_for = [&](int64_t units) {
+        const int64_t gy = std::min<int64_t>(BH, 65535);
+        const int64_t want_x = std::max<int64_t>(1, ((int64_t)h->num_cus * 32 + gy - 1) / gy);  // enough blocks to fill the chip
+        return dim3((unsigned)std::min<int64_t>((units + 255) / 256, want_x), (unsigned)gy);
+    };
     if (vec) {
-        const int64_t f = 16 / es, total = BH * len / f;
-        const unsigned grid = (unsigned)std::min<int64_t>((total + 255) / 256, (int64_t)h->num_cus * 16);
-        hipLaunchKernelGGL(nfd::kvcache_append_vec16, dim3(grid), dim3(256), 0, st, (nfd::u32x4*)kd, (nfd::u32x4*)vd,
+        const int64_t f = 16 / es;
+        hipLaunchKernelGGL(nfd::kvcache_copy<nfd::u32x4>, grid_for(len / f), block, 0, st, (nfd::u32x4*)kd, (nfd::u32x4*)vd,
                            (const nfd::u32x4*)ks, (const nfd::u32x4*)vs, head_dst / f, head_src / f, off_dst / f,
-                           off_src / f, len / f, total);
+                           off_src / f, len / f, BH);
+    } else if (es == 2) {
+        hipLaunchKernelGGL(nfd::kvcache_copy<uint16_t>, grid_for(len), block, 0, st, (uint16_t*)kd, (uint16_t*)vd,
+                           (const uint16_t*)ks, (const uint16_t*)vs, head_dst, head_src, off_dst, off_src, len, BH);
     } else {
-        const int64_t total = BH * len;
-        const unsigned grid = (unsigned)std::min<int64_t>((total + 255) / 256, (int64_t)h->num_cus * 16);
-        if (es == 2)
-            hipLaunchKernelGGL(nfd::kvcache_append_elem<uint16_t>, dim3(grid), dim3(256), 0, st, (uint16_t*)kd,
-                               (uint16_t*)vd, (const uint16_t*)ks, (const uint16_t*)vs, head_dst, head_src, off_dst,
-                               off_src, len, total);
-        else
-            hipLaunchKernelGGL(nfd::kvcache_append_elem<uint32_t>, dim3(grid), dim3(256), 0, st, (uint32_t*)kd,
-                               (uint32_t*)vd, (const uint32_t*)ks, (const uint32_t*)vs, head_dst, head_src, off_dst,
-                               off_src, len, total);
+        hipLaunchKernelGGL(nfd::kvcache_copy<uint32_t>, grid_for(len), block, 0, st, (uint32_t*)kd, (uint32_t*)vd,
+                           (const uint32_t*)ks, (const uint32_t*)vs, head_dst, head_src, off_dst, off_src, len, BH);
     }
 }
 
