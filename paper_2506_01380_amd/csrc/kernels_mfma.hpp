@@ -37,7 +37,7 @@ namespace mfma {
 
 constexpr int kD = 64;                        // head width
 constexpr int kBN = 64;                       // keys per tile
-constexpr int kBM = 256;                      // query rows per workgroup
+constexpr int kBM = 256;                      // query rows per workgroup (throughput shape; 128 in the latency shape)
 constexpr int kWaves = 4;                     // wavefronts per workgroup, 64 query rows each
 constexpr int kTileElems = kBN * kD;          // 4096 bf16 = 8 KB, rows of 128 B, no padding
 constexpr int kRingSlots = 3;                 // K and V ring depth (tiles)
@@ -112,11 +112,12 @@ __device__ __forceinline__ WorkItem decode_work(const FwdParams& p) {
 // Final write of one wavefront's 64 query rows: normalised bf16 output when the keys were not
 // split, otherwise the unnormalised fp32 accumulator plus (reference max in log2 units, row sum).
 // Lane (n, h) holds, for query column n of block qt, output features 32*dt + 8*rb + 4*h + 0..3.
-__device__ __forceinline__ void store_rows(const FwdParams& p, const WorkItem& wi, const int (&row)[2], int h,
-                                           const f32x16 (&o_acc)[2][2], const float (&l_sum)[2],
-                                           const float (&m_used)[2], float c) {
+template <int QT>
+__device__ __forceinline__ void store_rows(const FwdParams& p, const WorkItem& wi, const int (&row)[QT], int h,
+                                           const f32x16 (&o_acc)[2][QT], const float (&l_sum)[QT],
+                                           const float (&m_used)[QT], float c) {
 #pragma unroll
-    for (int qt = 0; qt < 2; ++qt) {
+    for (int qt = 0; qt < QT; ++qt) {
         const float l_row = l_sum[qt] + __shfl_xor(l_sum[qt], 32);
         if (row[qt] >= p.Sq) continue;
         if (p.n_splits == 1) {
@@ -151,9 +152,15 @@ __device__ __forceinline__ void store_rows(const FwdParams& p, const WorkItem& w
     }
 }
 
-__global__ void __launch_bounds__(kWaves * 64, 2)
+// QT = 2: 64 query rows per wavefront, 256 per workgroup, two wavefronts per SIMD: the throughput shape.
+// QT = 1: 32 rows per wavefront, 128 per workgroup, three wavefronts per SIMD: half the softmax and half the
+// matrix work per tile and wavefront, i.e. a shorter chain per key tile, for calls with few query rows whose
+// time is the length of that chain (cached forms); it reads twice the LDS bytes per FLOP.
+template <int QT>
+__global__ void __launch_bounds__(kWaves * 64, QT == 2 ? 2 : 3)
 attn_fwd_bf16_d64(FwdParams p) {
-    constexpr int BM = kBM;
+    constexpr int BM = kWaves * 32 * QT;
+    constexpr int WR = 32 * QT;  // query rows per wavefront
     constexpr int PRIO = kMfmaPriority;
     __shared__ SmemRing sm;
     const WorkItem wi = decode_work(p);
@@ -175,31 +182,33 @@ attn_fwd_bf16_d64(FwdParams p) {
     const __bf16* vg = (const __bf16*)p.v + (int64_t)wi.bh * p.Scap * kD;
 
     // ---- this wavefront's queries -------------------------------------------------------
-    const int rw0 = r0 + wave * 64;
-    int row[2], kmax_lane[2];
-    bf16x8 qf[2][4];
+    const int rw0 = r0 + wave * WR;
+    int row[QT], kmax_lane[QT];
+    bf16x8 qf[QT][4];
 #pragma unroll
-    for (int qt = 0; qt < 2; ++qt) {
+    for (int qt = 0; qt < QT; ++qt) {
         row[qt] = rw0 + 32 * qt + n;
         const int rc = min(row[qt], p.Sq - 1);  // ragged tail: compute a duplicate, never store it
         kmax_lane[qt] = kmax_of_row(rc, p.T, p.P);
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) qf[qt][ks] = *(const bf16x8*)(qg + (int64_t)rc * kD + 16 * ks + 8 * h);
     }
-    const int rw_first = min(rw0, p.Sq - 1), rw_last = min(rw0 + 63, p.Sq - 1);
+    const int rw_first = min(rw0, p.Sq - 1), rw_last = min(rw0 + WR - 1, p.Sq - 1);
     const int kmin_wave = kmax_of_row(rw_first, p.T, p.P);  // tiles ending at or below need no mask
     const int kmax_wave = kmax_of_row(rw_last, p.T, p.P);   // tiles starting at or above are skipped
     const bool wave_active = rw0 < p.Sq;
 
-    f32x16 o_acc[2][2];  // [dt][qt]: O^T rows 32*dt.., query block qt
+    f32x16 o_acc[2][QT];  // [dt][qt]: O^T rows 32*dt.., query block qt
 #pragma unroll
     for (int a = 0; a < 2; ++a)
 #pragma unroll
-        for (int b = 0; b < 2; ++b)
+        for (int b = 0; b < QT; ++b)
 #pragma unroll
             for (int r = 0; r < 16; ++r) o_acc[a][b][r] = 0.f;
-    float m_used[2] = {kNegBig, kNegBig};  // reference max, raw score units (stale by design)
-    float l_sum[2] = {0.f, 0.f};           // this lane's share of the row sum
+    float m_used[QT];  // reference max, raw score units (stale by design)
+    float l_sum[QT];   // this lane's share of the row sum
+#pragma unroll
+    for (int qt = 0; qt < QT; ++qt) { m_used[qt] = kNegBig; l_sum[qt] = 0.f; }
     const float c = p.scale_log2e;
 
     // ---- tile loads: one wave instruction fills 8 consecutive tile rows (1 KB); a wavefront owns
@@ -251,7 +260,7 @@ attn_fwd_bf16_d64(FwdParams p) {
             const __bf16* ks_ = sm.k[slot];
             const __bf16* vs_ = sm.v[slot];
             // ---- S^T = K . Q^T: all eight K fragments are requested before the first product ------
-            f32x16 s_acc[2][2];  // [kb][qt]
+            f32x16 s_acc[2][QT];  // [kb][qt]
             bf16x8 kf[2][4];
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb)
@@ -266,13 +275,13 @@ attn_fwd_bf16_d64(FwdParams p) {
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb) {
 #pragma unroll
-                for (int qt = 0; qt < 2; ++qt)
+                for (int qt = 0; qt < QT; ++qt)
 #pragma unroll
                     for (int r = 0; r < 16; ++r) s_acc[kb][qt][r] = 0.f;
 #pragma unroll
                 for (int ks = 0; ks < 4; ++ks)
 #pragma unroll
-                    for (int qt = 0; qt < 2; ++qt)
+                    for (int qt = 0; qt < QT; ++qt)
                         s_acc[kb][qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kb][ks], qf[qt][ks], s_acc[kb][qt], 0, 0, 0);
             }
             __builtin_amdgcn_sched_barrier(0);
@@ -298,7 +307,7 @@ attn_fwd_bf16_d64(FwdParams p) {
 #pragma unroll
                 for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-                    for (int qt = 0; qt < 2; ++qt)
+                    for (int qt = 0; qt < QT; ++qt)
 #pragma unroll
                         for (int r = 0; r < 16; ++r) {
                             const int key = j0 + 32 * kb + 8 * (r >> 2) + 4 * h + (r & 3);
@@ -306,12 +315,12 @@ attn_fwd_bf16_d64(FwdParams p) {
                         }
             }
             // ---- optimistic softmax, lane-local per query column -------------------------------
-            bf16x8 pf[2][2][2];  // [kb][g][qt]
-            float l_tile[2];
+            bf16x8 pf[2][2][QT];  // [kb][g][qt]
+            float l_tile[QT];
             auto form_p = [&]() {  // P = exp2(c*s - c*m_used) in bf16; row sums by plain fp32 adds (the
                                    // packed dot instruction shares the matrix pipe and would stall MFMAs)
 #pragma unroll
-                for (int qt = 0; qt < 2; ++qt) {
+                for (int qt = 0; qt < QT; ++qt) {
                     const float mc = m_used[qt] * c;
                     float l = 0.f, l2 = 0.f;
 #pragma unroll
@@ -340,15 +349,17 @@ attn_fwd_bf16_d64(FwdParams p) {
 #pragma unroll
                 for (int b = 0; b < 2; ++b)
 #pragma unroll
-                    for (int e = 0; e < 2; ++e) asm volatile("" : "+v"(pf[a][b][e]));
+                    for (int e = 0; e < QT; ++e) asm volatile("" : "+v"(pf[a][b][e]));
             // V^T fragments are requested once P is formed (earlier they would not fit the register
             // file next to the scores kept for the rare exact pass); the latency passes behind the
             // overflow test and the other wavefront of the SIMD.
             read_v_frags();
-            const bool bad = !(l_tile[0] < kOptimisticLimit) | !(l_tile[1] < kOptimisticLimit);
+            bool bad = false;
+#pragma unroll
+            for (int qt = 0; qt < QT; ++qt) bad |= !(l_tile[qt] < kOptimisticLimit);
             if (__builtin_amdgcn_ballot_w64(bad) != 0) {  // exact path: this tile's max, rescale, redo
 #pragma unroll
-                for (int qt = 0; qt < 2; ++qt) {
+                for (int qt = 0; qt < QT; ++qt) {
                     float a = fmaxf(s_acc[0][qt][0], s_acc[1][qt][0]);
 #pragma unroll
                     for (int r = 1; r < 16; ++r) a = fmaxf(fmaxf(a, s_acc[0][qt][r]), s_acc[1][qt][r]);
@@ -364,8 +375,8 @@ attn_fwd_bf16_d64(FwdParams p) {
                 }
                 form_p();
             }
-            l_sum[0] += l_tile[0];
-            l_sum[1] += l_tile[1];
+#pragma unroll
+            for (int qt = 0; qt < QT; ++qt) l_sum[qt] += l_tile[qt];
             // ---- O^T += V^T . P^T -----------------------------------------------------------------
             __builtin_amdgcn_sched_barrier(0);
             __builtin_amdgcn_s_setprio(PRIO);
@@ -376,7 +387,7 @@ attn_fwd_bf16_d64(FwdParams p) {
 #pragma unroll
                     for (int dt = 0; dt < 2; ++dt)
 #pragma unroll
-                        for (int qt = 0; qt < 2; ++qt)
+                        for (int qt = 0; qt < QT; ++qt)
                             o_acc[dt][qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[kb][g][dt], pf[kb][g][qt], o_acc[dt][qt], 0, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
         }
@@ -399,7 +410,7 @@ attn_fwd_bf16_d64(FwdParams p) {
     }
 
     if (!wave_active) return;
-    store_rows(p, wi, row, h, o_acc, l_sum, m_used, c);
+    store_rows<QT>(p, wi, row, h, o_acc, l_sum, m_used, c);
 }
 
 // Merge the key-split partials of one query row: out = sum_s w_s O_s / sum_s w_s l_s with

@@ -79,23 +79,44 @@ int nfd_attn_plan(nfd_dtype_t dtype, int B, int H, int F, int T, int D, int kv_f
     nfd_attn_plan_t pl{};
     if (dtype == NFD_BF16 && D == nfd::mfma::kD) {
         pl.kernel = 1;
-        pl.block_m = nfd::mfma::kBM;
         pl.block_n = nfd::mfma::kBN;
-        pl.n_q_tiles = (int)((Sq + pl.block_m - 1) / pl.block_m);
         int64_t visited = 0, max_tiles = 0;
-        for (int qt = 0; qt < pl.n_q_tiles; ++qt) {
-            const int64_t r_last = std::min<int64_t>((int64_t)(qt + 1) * pl.block_m, Sq) - 1;
-            const int64_t nt = (kmax_rows(r_last, T, P) + pl.block_n - 1) / pl.block_n;
-            visited += nt;
-            max_tiles = std::max(max_tiles, nt);
+        auto tile_counts = [&](int block_m) {
+            pl.block_m = block_m;
+            pl.n_q_tiles = (int)((Sq + block_m - 1) / block_m);
+            visited = 0;
+            max_tiles = 0;
+            for (int qt = 0; qt < pl.n_q_tiles; ++qt) {
+                const int64_t r_last = std::min<int64_t>((int64_t)(qt + 1) * block_m, Sq) - 1;
+                const int64_t nt = (kmax_rows(r_last, T, P) + pl.block_n - 1) / pl.block_n;
+                visited += nt;
+                max_tiles = std::max(max_tiles, nt);
+            }
+        };
+        // 256-row workgroups (64 rows per wavefront, 2 workgroups per CU) are the throughput shape.  When
+        // there are very few query rows (single-frame decode of one sequence), the call's time is the
+        // length of a workgroup's chain of key tiles, and 128-row workgroups (32 rows per wavefront, 3 per
+        // CU) make the links of it shorter: measured -7 % at one frame of 336 queries x 16 heads, +-2 % at two
+        // frames, a loss from four frames on (twice the LDS traffic per FLOP).
+        tile_counts(nfd::mfma::kBM);
+        int wg_per_cu = 2;
+        if (BH * pl.n_q_tiles * 4 < (int64_t)num_cus) {
+            tile_counts(nfd::mfma::kBM / 2);
+            wg_per_cu = 3;
         }
+#ifdef NFD_TUNE_SPLITS  // development build: force the workgroup shape from the environment
+        if (const char* e = getenv("NFD_BM")) {
+            tile_counts(atoi(e) == 128 ? 128 : 256);
+            wg_per_cu = atoi(e) == 128 ? 3 : 2;
+        }
+#endif
         // Key splits: only when the query tiles alone cannot fill the chip (cached forms).  The count
         // minimises a small cost model in units of the time one workgroup needs for one key tile when
         // two workgroups share a CU: workgroups run in rounds of 2 per CU; a workgroup that has its CU
         // to itself is about 1.2x faster (measured); every workgroup pays a fixed prologue/epilogue of
         // about three tiles; the combine pass costs a launch plus the write and read of the partials,
         // which grows with rows x splits (about one unit per 15000 row-partials at HBM speed).
-        const int64_t slots = (int64_t)num_cus * 2, base = BH * pl.n_q_tiles;
+        const int64_t slots = (int64_t)num_cus * wg_per_cu, base = BH * pl.n_q_tiles;
         int splits = 1;
         if (base < slots) {
             const size_t per_split = (size_t)(BH * Sq) * (nfd::mfma::kD + 2) * sizeof(float);
@@ -105,7 +126,7 @@ int nfd_attn_plan(nfd_dtype_t dtype, int B, int H, int F, int T, int D, int kv_f
                 const int64_t wgs = base * s;
                 const int64_t rounds = (wgs + slots - 1) / slots;
                 const double len = (double)((max_tiles + s - 1) / s) + 3.0;
-                const double pace = wgs <= num_cus ? 0.83 : 1.0;
+                const double pace = wgs * 2 <= slots ? 0.83 : 1.0;
                 const double combine = s > 1 ? 1.0 + (double)s * (double)(BH * Sq) / 15000.0 : 0.0;
                 const double cost = rounds * len * pace + combine;
                 if (cost < best) { best = cost; splits = s; }
@@ -225,7 +246,10 @@ static int fwd_impl(nfd_attn_t* h, const void* q, const void* k, const void* v, 
     hipStream_t st = (hipStream_t)stream;
 
     if (pl.kernel == 1) {
-        hipLaunchKernelGGL(nfd::mfma::attn_fwd_bf16_d64, dim3(pl.n_workgroups), dim3(nfd::mfma::kWaves * 64), 0, st, p);
+        if (pl.block_m == nfd::mfma::kBM)
+            hipLaunchKernelGGL(nfd::mfma::attn_fwd_bf16_d64<2>, dim3(pl.n_workgroups), dim3(nfd::mfma::kWaves * 64), 0, st, p);
+        else
+            hipLaunchKernelGGL(nfd::mfma::attn_fwd_bf16_d64<1>, dim3(pl.n_workgroups), dim3(nfd::mfma::kWaves * 64), 0, st, p);
         if (pl.n_splits > 1) {
             const int64_t total = (int64_t)p.BH * p.Sq * (nfd::mfma::kD / 4);
             hipLaunchKernelGGL(nfd::mfma::attn_combine_d64, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, p);
