@@ -341,22 +341,25 @@ attn_fwd_bf16_d64(FwdParams p) {
                     l_tile[qt] = l + l2;
                 }
             };
-            form_p();
-            // Pin the packed P before the test: otherwise the compiler, seeing P rebuilt on the rare
-            // path, postpones the conversions until after the branch and keeps 64 exponentials alive.
+            bool bad = true;  // a workgroup's first tile has no reference yet: straight to the exact pass
+            if (t != t_begin) {
+                form_p();
+                // Pin the packed P before the test: otherwise the compiler, seeing P rebuilt on the rare
+                // path, postpones the conversions until after the branch and keeps 64 exponentials alive.
 #pragma unroll
-            for (int a = 0; a < 2; ++a)
+                for (int a = 0; a < 2; ++a)
 #pragma unroll
-                for (int b = 0; b < 2; ++b)
+                    for (int b = 0; b < 2; ++b)
 #pragma unroll
-                    for (int e = 0; e < QT; ++e) asm volatile("" : "+v"(pf[a][b][e]));
+                        for (int e = 0; e < QT; ++e) asm volatile("" : "+v"(pf[a][b][e]));
+                bad = false;
+#pragma unroll
+                for (int qt = 0; qt < QT; ++qt) bad |= !(l_tile[qt] < kOptimisticLimit);
+            }
             // V^T fragments are requested once P is formed (earlier they would not fit the register
             // file next to the scores kept for the rare exact pass); the latency passes behind the
             // overflow test and the other wavefront of the SIMD.
             read_v_frags();
-            bool bad = false;
-#pragma unroll
-            for (int qt = 0; qt < QT; ++qt) bad |= !(l_tile[qt] < kOptimisticLimit);
             if (__builtin_amdgcn_ballot_w64(bad) != 0) {  // exact path: this tile's max, rescale, redo
 #pragma unroll
                 for (int qt = 0; qt < QT; ++qt) {
