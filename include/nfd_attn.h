@@ -243,6 +243,13 @@ typedef struct nfd_attn_plan {
 int nfd_attn_plan(nfd_dtype_t dtype, int B, int H, int F, int T, int D, int kv_frames,
                   int q_frames, int num_cus, size_t workspace_limit, nfd_attn_plan_t* plan);
 
+/* Which (head, query tile, key split) workgroup `block` of the matrix-core forward launch works on: the
+ * same function the kernel evaluates, exposed so that the schedule can be checked without a GPU (every item
+ * exactly once over blocks 0 .. n_workgroups-1).  group_q_tiles: the ordering used when K/V exceed the
+ * last-level cache.  Errors: NFD_ERR_NULL, NFD_ERR_SHAPE (also a block past the launch). */
+int nfd_attn_work_item(int BH, int n_q_tiles, int n_splits, int group_q_tiles, unsigned block, int* bh, int* q_tile,
+                       int* split);
+
 /* Visible (query, key) pairs per (b, h): T^2 (q_frames P + q_frames (q_frames + 1) / 2). */
 int64_t nfd_attn_visible_pairs(int T, int kv_frames, int q_frames);
 

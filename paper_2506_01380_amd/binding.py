@@ -26,7 +26,7 @@ EXPORTS = (
     "nfd_last_error", "nfd_attn_check_args", "nfd_attn_plan", "nfd_attn_visible_pairs",
     "nfd_rope_kvcache_append", "nfd_rope_check_args",
     "nfd_block_causal_attn_fwd_lse", "nfd_block_causal_attn_bwd",
-    "nfd_kvcache_shift", "nfd_spec_init", "nfd_spec_next", "nfd_spec_accept",
+    "nfd_kvcache_shift", "nfd_spec_init", "nfd_spec_next", "nfd_spec_accept", "nfd_attn_work_item",
 )
 
 
@@ -104,6 +104,8 @@ def lib():
         L.nfd_attn_check_args.restype = ci
         L.nfd_attn_plan.argtypes = [ci] * 9 + [ctypes.c_size_t, ctypes.POINTER(Plan)]
         L.nfd_attn_plan.restype = ci
+        L.nfd_attn_work_item.argtypes = [ci] * 4 + [ctypes.c_uint] + [ctypes.POINTER(ci)] * 3
+        L.nfd_attn_work_item.restype = ci
         L.nfd_attn_visible_pairs.argtypes = [ci] * 3
         L.nfd_attn_visible_pairs.restype = ctypes.c_int64
         _lib = L
@@ -222,6 +224,14 @@ def nfd_attn_plan(dtype, B, H, F, T, D, kv_frames, q_frames, num_cus=0, workspac
     _check(lib().nfd_attn_plan(dtype, B, H, F, T, D, kv_frames, q_frames, num_cus, workspace_limit,
                                ctypes.byref(pl)), "nfd_attn_plan")
     return pl.as_dict()
+
+
+def nfd_attn_work_item(BH, n_q_tiles, n_splits, group_q_tiles, block):
+    """(bh, q_tile, split) of workgroup ``block``, or None past the end of the launch."""
+    bh, qt, sp = ctypes.c_int(), ctypes.c_int(), ctypes.c_int()
+    rc = lib().nfd_attn_work_item(BH, n_q_tiles, n_splits, int(group_q_tiles), block, ctypes.byref(bh), ctypes.byref(qt),
+                                  ctypes.byref(sp))
+    return (bh.value, qt.value, sp.value) if rc == NFD_OK else None
 
 
 def nfd_attn_visible_pairs(T, kv_frames, q_frames):

@@ -85,28 +85,32 @@ struct WorkItem {
     int bh, q_tile, split;
     bool valid;
 };
-__device__ __forceinline__ WorkItem decode_work(const FwdParams& p) {
+__host__ __device__ __forceinline__ WorkItem work_item_of(unsigned block, int BH, int n_q_tiles, int n_splits,
+                                                          int group_q_tiles) {
     WorkItem w;
-    const int per_head = p.n_q_tiles * p.n_splits;
-    const bool pinned = (p.BH & 7) == 0;
-    const int xcd = pinned ? (int)(blockIdx.x & 7) : 0;
-    const int j = pinned ? (int)(blockIdx.x >> 3) : (int)blockIdx.x;
-    const int hh = pinned ? p.BH >> 3 : p.BH;  // heads this id stream runs over
+    const int per_head = n_q_tiles * n_splits;
+    const bool pinned = (BH & 7) == 0;
+    const int xcd = pinned ? (int)(block & 7) : 0;
+    const int j = pinned ? (int)(block >> 3) : (int)block;
+    const int hh = pinned ? BH >> 3 : BH;  // heads this id stream runs over
     w.valid = j < hh * per_head;
     int head_local;
-    if (!p.group_q_tiles) {
+    if (!group_q_tiles) {
         const int item = j / hh;
         head_local = j % hh;
-        w.q_tile = p.n_q_tiles - 1 - item / p.n_splits;
-        w.split = item % p.n_splits;
+        w.q_tile = n_q_tiles - 1 - item / n_splits;
+        w.split = item % n_splits;
     } else {
-        const int rest = j / p.n_q_tiles;
-        w.q_tile = p.n_q_tiles - 1 - j % p.n_q_tiles;
+        const int rest = j / n_q_tiles;
+        w.q_tile = n_q_tiles - 1 - j % n_q_tiles;
         head_local = rest % hh;
         w.split = rest / hh;
     }
     w.bh = pinned ? head_local * 8 + xcd : head_local;
     return w;
+}
+__device__ __forceinline__ WorkItem decode_work(const FwdParams& p) {
+    return work_item_of(blockIdx.x, p.BH, p.n_q_tiles, p.n_splits, p.group_q_tiles);
 }
 
 // Final write of one wavefront's 64 query rows: normalised bf16 output when the keys were not

@@ -163,6 +163,16 @@ int nfd_attn_plan(nfd_dtype_t dtype, int B, int H, int F, int T, int D, int kv_f
     return NFD_OK;
 }
 
+int nfd_attn_work_item(int BH, int n_q_tiles, int n_splits, int group_q_tiles, unsigned block, int* bh, int* q_tile,
+                       int* split) {
+    if (!bh || !q_tile || !split) return NFD_ERR_NULL;
+    if (BH < 1 || n_q_tiles < 1 || n_splits < 1) return NFD_ERR_SHAPE;
+    const nfd::mfma::WorkItem w = nfd::mfma::work_item_of(block, BH, n_q_tiles, n_splits, group_q_tiles);
+    if (!w.valid) return NFD_ERR_SHAPE;
+    *bh = w.bh; *q_tile = w.q_tile; *split = w.split;
+    return NFD_OK;
+}
+
 int nfd_attn_create(nfd_attn_t** out, nfd_dtype_t dtype, int device, size_t workspace_bytes) {
     if (!out) return NFD_ERR_NULL;
     *out = nullptr;

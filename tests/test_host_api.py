@@ -109,3 +109,25 @@ def test_plan_refuses_a_launch_beyond_the_grid_limit():
     rc = nb.lib().nfd_attn_plan(nb.NFD_BF16, 1 << 12, 1 << 12, 1 << 14, 1 << 16, 64, 1 << 14, 1 << 14, 0, 0,
                                 __import__("ctypes").byref(nb.Plan()))
     assert rc == nb.NFD_ERR_UNSUPPORTED
+
+
+@pytest.mark.parametrize("BH,nq,ns", [(16, 2, 16), (16, 6, 5), (128, 3, 4), (5, 3, 7), (9, 4, 1), (64, 21, 1), (3, 1, 2),
+                                      (1, 1, 1), (17, 2, 3), (12, 3, 16), (24, 21, 1), (8, 1, 1)])
+@pytest.mark.parametrize("group", [0, 1])
+def test_every_work_item_is_dealt_exactly_once(BH, nq, ns, group):
+    """The workgroup -> (head, query tile, split) map of the forward launch is a bijection onto all items;
+    with a head count that is a multiple of 8 a head stays on one XCD (block id mod 8)."""
+    n = BH * nq * ns
+    seen = {}
+    for blk in range(n):
+        item = nb.nfd_attn_work_item(BH, nq, ns, group, blk)
+        assert item is not None and 0 <= item[0] < BH and 0 <= item[1] < nq and 0 <= item[2] < ns
+        assert item not in seen
+        seen[item] = blk
+    assert len(seen) == n and nb.nfd_attn_work_item(BH, nq, ns, group, n) is None
+    if BH % 8 == 0:
+        assert all(blk % 8 == bh % 8 for (bh, _, _), blk in seen.items())
+    if not group:  # heaviest (last) query tiles first
+        order = [nb.nfd_attn_work_item(BH, nq, ns, 0, b)[1] for b in range(n)]
+        first_of = {q: order.index(q) for q in range(nq)}
+        assert all(first_of[q + 1] <= first_of[q] for q in range(nq - 1))
