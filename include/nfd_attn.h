@@ -101,8 +101,9 @@ int nfd_block_causal_attn_fwd_lse(nfd_attn_t* h, const void* q, const void* k, c
  * out and lse are the results of nfd_block_causal_attn_fwd_lse on the same q, k, v, scale.  Of dk and
  * dv only the first kv_frames*T rows of every head are written.  No atomics: results are
  * bit-reproducible.  Uses the handle's workspace (4 bytes per query row).
- * Supported: bf16, D = 64 (any B, H, T, frames), tensors 16-byte aligned; everything else
- * NFD_ERR_UNSUPPORTED.
+ * Supported: as the forward - bf16 with D = 64 on the matrix-core path (tensors 16-byte aligned there),
+ * every other D <= 256 and all fp32 shapes on a general fp32-arithmetic path (one wavefront per row, not
+ * tuned).
  * Errors, in this order: NFD_ERR_NULL, NFD_ERR_SHAPE, NFD_ERR_CAPACITY, NFD_ERR_UNSUPPORTED,
  * NFD_ERR_ALLOC (workspace too small), NFD_ERR_HIP.
  */

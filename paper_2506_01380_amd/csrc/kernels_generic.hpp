@@ -87,6 +87,165 @@ attn_fwd_generic(FwdParams p) {
     if (p.lse && lane == 0) p.lse[row_id] = (m + log2f(l)) * kLn2;
 }
 
+// General backward: the same one-wavefront-per-row scheme, fp32 arithmetic, any T, D <= 256.  Two kernels,
+// neither with atomics.  With p_ij = exp(scale <q_i, k_j> - lse_i) over the visible keys of row i and
+// delta_i = <dout_i, out_i>:  ds_ij = p_ij (<dout_i, v_j> - delta_i),  dq_i = scale sum_j ds_ij k_j,
+// dk_j = scale sum_i ds_ij q_i,  dv_j = sum_i p_ij dout_i.
+struct BwdGenericParams {
+    const void *q, *k, *v, *out, *dout;
+    const float* lse;
+    float* delta;  // [BH, Sq], written by the dq kernel, read by the dk/dv kernel
+    void *dq, *dk, *dv;
+    int BH, Sq, Sk, Scap, T, P, D;
+    float scale, scale_log2e;
+};
+
+// One wavefront per query row: delta_i, then dq_i over the visible keys, 64 at a time.
+template <typename T>
+__global__ void __launch_bounds__(kGenericWaves * 64)
+attn_bwd_dq_generic(BwdGenericParams p) {
+    __shared__ float q_s[kGenericWaves][kGenericMaxD];
+    __shared__ float g_s[kGenericWaves][kGenericMaxD];
+    __shared__ float ds_s[kGenericWaves][64];
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int64_t row_id = (int64_t)blockIdx.x * kGenericWaves + w;  // over BH * Sq
+    if (row_id >= (int64_t)p.BH * p.Sq) return;
+    const int bh = (int)(row_id / p.Sq), i = (int)(row_id % p.Sq);
+    const int D = p.D;
+    const T* q = (const T*)p.q + row_id * D;
+    const T* o = (const T*)p.out + row_id * D;
+    const T* g = (const T*)p.dout + row_id * D;
+    const T* k = (const T*)p.k + (int64_t)bh * p.Scap * D;
+    const T* v = (const T*)p.v + (int64_t)bh * p.Scap * D;
+
+    float dsum = 0.f;
+    for (int d = lane; d < D; d += 64) {
+        const float gd = to_f32<T>(g[d]);
+        q_s[w][d] = to_f32<T>(q[d]);
+        g_s[w][d] = gd;
+        dsum = fmaf(gd, to_f32<T>(o[d]), dsum);
+    }
+    const float delta = wave_sum(dsum);
+    if (lane == 0) p.delta[row_id] = delta;
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_s_waitcnt(0xc07f);
+
+    const float lse2 = p.lse[row_id] * kLog2e;
+    const int kmax = kmax_of_row(i, p.T, p.P);
+    float acc[kGenericMaxD / 64] = {0.f, 0.f, 0.f, 0.f};
+    for (int j0 = 0; j0 < kmax; j0 += 64) {
+        const int j = j0 + lane;
+        float ds = 0.f;
+        if (j < kmax) {
+            const T* kr = k + (int64_t)j * D;
+            const T* vr = v + (int64_t)j * D;
+            float a = 0.f, b = 0.f;
+            for (int d = 0; d < D; ++d) {
+                a = fmaf(q_s[w][d], to_f32<T>(kr[d]), a);
+                b = fmaf(g_s[w][d], to_f32<T>(vr[d]), b);
+            }
+            ds = exp2f(a * p.scale_log2e - lse2) * (b - delta);
+        }
+        ds_s[w][lane] = ds;
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_s_waitcnt(0xc07f);
+        const int nj = min(64, kmax - j0);
+#pragma unroll
+        for (int c = 0; c < kGenericMaxD / 64; ++c) {
+            const int d = lane + 64 * c;
+            if (d < D) {
+                float a = acc[c];
+                for (int jj = 0; jj < nj; ++jj) a = fmaf(ds_s[w][jj], to_f32<T>(k[(int64_t)(j0 + jj) * D + d]), a);
+                acc[c] = a;
+            }
+        }
+        __builtin_amdgcn_wave_barrier();
+    }
+    T* dq = (T*)p.dq + row_id * D;
+#pragma unroll
+    for (int c = 0; c < kGenericMaxD / 64; ++c) {
+        const int d = lane + 64 * c;
+        if (d < D) dq[d] = from_f32<T>(acc[c] * p.scale);
+    }
+}
+
+// One wavefront per key row j < Sk: dk_j and dv_j over the query rows that see it, 64 at a time.  Those are
+// the rows from (floor(j/T) - P) * T on (none below 0): every later frame sees the key as well.
+template <typename T>
+__global__ void __launch_bounds__(kGenericWaves * 64)
+attn_bwd_dkdv_generic(BwdGenericParams p) {
+    __shared__ float k_s[kGenericWaves][kGenericMaxD];
+    __shared__ float v_s[kGenericWaves][kGenericMaxD];
+    __shared__ float p_s[kGenericWaves][64];
+    __shared__ float ds_s[kGenericWaves][64];
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int64_t key_id = (int64_t)blockIdx.x * kGenericWaves + w;  // over BH * Sk
+    if (key_id >= (int64_t)p.BH * p.Sk) return;
+    const int bh = (int)(key_id / p.Sk), j = (int)(key_id % p.Sk);
+    const int D = p.D;
+    const T* kr = (const T*)p.k + ((int64_t)bh * p.Scap + j) * D;
+    const T* vr = (const T*)p.v + ((int64_t)bh * p.Scap + j) * D;
+    const T* q = (const T*)p.q + (int64_t)bh * p.Sq * D;
+    const T* g = (const T*)p.dout + (int64_t)bh * p.Sq * D;
+    const float* lse = p.lse + (int64_t)bh * p.Sq;
+    const float* delta = p.delta + (int64_t)bh * p.Sq;
+
+    for (int d = lane; d < D; d += 64) {
+        k_s[w][d] = to_f32<T>(kr[d]);
+        v_s[w][d] = to_f32<T>(vr[d]);
+    }
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_s_waitcnt(0xc07f);
+
+    const int rmin = max(0, (j / p.T - p.P) * p.T);
+    float acc_k[kGenericMaxD / 64] = {0.f, 0.f, 0.f, 0.f};
+    float acc_v[kGenericMaxD / 64] = {0.f, 0.f, 0.f, 0.f};
+    for (int i0 = rmin; i0 < p.Sq; i0 += 64) {
+        const int i = i0 + lane;
+        float pij = 0.f, ds = 0.f;
+        if (i < p.Sq) {
+            const T* qr = q + (int64_t)i * D;
+            const T* gr = g + (int64_t)i * D;
+            float a = 0.f, b = 0.f;
+            for (int d = 0; d < D; ++d) {
+                a = fmaf(to_f32<T>(qr[d]), k_s[w][d], a);
+                b = fmaf(to_f32<T>(gr[d]), v_s[w][d], b);
+            }
+            pij = exp2f(a * p.scale_log2e - lse[i] * kLog2e);
+            ds = pij * (b - delta[i]);
+        }
+        p_s[w][lane] = pij;
+        ds_s[w][lane] = ds;
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_s_waitcnt(0xc07f);
+        const int ni = min(64, p.Sq - i0);
+#pragma unroll
+        for (int c = 0; c < kGenericMaxD / 64; ++c) {
+            const int d = lane + 64 * c;
+            if (d < D) {
+                float ak = acc_k[c], av = acc_v[c];
+                for (int ii = 0; ii < ni; ++ii) {
+                    ak = fmaf(ds_s[w][ii], to_f32<T>(q[(int64_t)(i0 + ii) * D + d]), ak);
+                    av = fmaf(p_s[w][ii], to_f32<T>(g[(int64_t)(i0 + ii) * D + d]), av);
+                }
+                acc_k[c] = ak;
+                acc_v[c] = av;
+            }
+        }
+        __builtin_amdgcn_wave_barrier();
+    }
+    T* dk = (T*)p.dk + ((int64_t)bh * p.Scap + j) * D;
+    T* dv = (T*)p.dv + ((int64_t)bh * p.Scap + j) * D;
+#pragma unroll
+    for (int c = 0; c < kGenericMaxD / 64; ++c) {
+        const int d = lane + 64 * c;
+        if (d < D) {
+            dk[d] = from_f32<T>(acc_k[c] * p.scale);
+            dv[d] = from_f32<T>(acc_v[c]);
+        }
+    }
+}
+
 // Copy a run of whole frames of every head between two head-strided tensors: the cache write of new
 // frames (Appendix B, KV caching) and the moves of the sliding context window.  K and V together.
 // All counts in units of the element type E (a 16-byte vector when every size and address allows it,

@@ -293,9 +293,34 @@ int nfd_block_causal_attn_bwd(nfd_attn_t* h, const void* q, const void* k, const
         return fail(h, NFD_ERR_NULL, "all tensors of the backward call must be non-null");
     const int rc = nfd_attn_check_args(h->dtype, B, H, F, T, D, kv_frames, q_frames);
     if (rc != NFD_OK) return fail(h, rc, "invalid shape arguments");
-    if (h->dtype != NFD_BF16 || D != nfd::mfma::kD)
-        return fail(h, NFD_ERR_UNSUPPORTED, "the backward is built for bf16 and head width 64");
     const int64_t BH = (int64_t)B * H, Sq = (int64_t)q_frames * T, Sk = (int64_t)kv_frames * T;
+    if (h->dtype != NFD_BF16 || D != nfd::mfma::kD) {
+        // general path: fp32 arithmetic, one wavefront per row
+        if ((size_t)(BH * Sq) * sizeof(float) > h->workspace_bytes)
+            return fail(h, NFD_ERR_ALLOC, "the per-row workspace of the backward exceeds the handle's workspace");
+        const int64_t gq = (BH * Sq + nfd::kGenericWaves - 1) / nfd::kGenericWaves;
+        const int64_t gk = (BH * Sk + nfd::kGenericWaves - 1) / nfd::kGenericWaves;
+        if (gq > (int64_t)0x7fffffff || gk > (int64_t)0x7fffffff)
+            return fail(h, NFD_ERR_UNSUPPORTED, "too many rows for one launch of the general backward");
+        if (!(scale > 0.f)) scale = 1.0f / std::sqrt((float)D);
+        nfd::BwdGenericParams g{};
+        g.q = q; g.k = k; g.v = v; g.out = out; g.dout = dout; g.lse = lse;
+        g.delta = (float*)h->workspace;
+        g.dq = dq; g.dk = dk; g.dv = dv;
+        g.BH = (int)BH; g.Sq = (int)Sq; g.Sk = (int)Sk; g.Scap = F * T; g.T = T; g.P = kv_frames - q_frames; g.D = D;
+        g.scale = scale;
+        g.scale_log2e = scale * nfd::kLog2e;
+        hipStream_t gs = (hipStream_t)stream;
+        const dim3 blk(nfd::kGenericWaves * 64);
+        if (h->dtype == NFD_BF16) {
+            hipLaunchKernelGGL(nfd::attn_bwd_dq_generic<__bf16>, dim3((unsigned)gq), blk, 0, gs, g);
+            hipLaunchKernelGGL(nfd::attn_bwd_dkdv_generic<__bf16>, dim3((unsigned)gk), blk, 0, gs, g);
+        } else {
+            hipLaunchKernelGGL(nfd::attn_bwd_dq_generic<float>, dim3((unsigned)gq), blk, 0, gs, g);
+            hipLaunchKernelGGL(nfd::attn_bwd_dkdv_generic<float>, dim3((unsigned)gk), blk, 0, gs, g);
+        }
+        return check_hip(h, hipGetLastError(), "general backward launch");
+    }
     if (((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)out | (uintptr_t)dout | (uintptr_t)dq | (uintptr_t)dk |
          (uintptr_t)dv) % 16 != 0 || (uintptr_t)lse % 4 != 0)
         return fail(h, NFD_ERR_UNSUPPORTED, "tensors must be 16-byte aligned (lse 4-byte)");

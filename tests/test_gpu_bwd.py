@@ -152,5 +152,58 @@ def test_backward_error_codes(attn):
         nb.nfd_block_causal_attn_bwd(attn.h, qd, kd, vd, out, out, lse, qd, kd, vd, B, H, 2, T, D, 3, 2)
     assert e.value.code == nb.NFD_ERR_CAPACITY
     with pytest.raises(nb.NfdError) as e:
-        nb.nfd_block_causal_attn_bwd(attn.h, qd, kd, vd, out, out, lse, qd, kd, vd, B, H, 2, T, 32, 2, 2)
-    assert e.value.code == nb.NFD_ERR_UNSUPPORTED
+        nb.nfd_block_causal_attn_bwd(attn.h, qd, kd, vd, out, out, lse, qd, kd, vd, B, H, 2, T, 512, 2, 2)
+    assert e.value.code == nb.NFD_ERR_UNSUPPORTED  # head width beyond the general path's 256
+
+
+GENERAL_CASES = [
+    # dtype, B, H, T, D, kvf, qf, F
+    ("fp32", 1, 2, 16, 64, 4, 4, 4),
+    ("fp32", 2, 3, 40, 32, 5, 5, 5),     # rows and keys not multiples of 64
+    ("fp32", 1, 2, 100, 64, 6, 2, 8),    # cached form with spare capacity
+    ("fp32", 1, 1, 1, 48, 130, 130, 130),  # T = 1, D not a multiple of 64
+    ("fp32", 1, 1, 336, 128, 2, 2, 2),   # the paper's frame size, two feature chunks per lane
+    ("bf16", 1, 2, 24, 32, 6, 6, 6),     # bf16 storage at a head width the matrix-core path is not built for
+    ("bf16", 1, 1, 50, 160, 3, 2, 3),
+]
+
+
+@pytest.mark.parametrize("dtype,B,H,T,D,kvf,qf,F", GENERAL_CASES)
+def test_backward_general_path(dtype, B, H, T, D, kvf, qf, F):
+    """fp32 storage, and head widths other than 64: the general kernels.  fp32 gradients within 1e-4
+    max-abs of the fp64 oracle (fp32 sums of at most a few thousand terms of magnitude <= 1 each
+    carry about 1e-6); bf16 storage to the bf16 bound of the other tests."""
+    seed = wl.BASE_SEED + 900 + T + D
+    q, k, v = wl.make_qkv(B, H, D, T, kvf, qf, F, dtype, seed=seed)
+    g = np.random.default_rng(seed + 1).standard_normal(q.shape).astype(np.float32)
+    tdt = torch.float32 if dtype == "fp32" else torch.bfloat16
+    if dtype == "bf16":
+        g = wl.round_to_bf16(g)
+    if F > kvf:
+        k[:, :, kvf * T:] = np.nan
+        v[:, :, kvf * T:] = np.nan
+    dev = lambda x: torch.from_numpy(x).cuda().to(tdt)
+    a = nb.Attention(dtype)
+    try:
+        qd, kd, vd, gd = dev(q), dev(k), dev(v), dev(g)
+        out, lse = a.forward_lse(qd, kd, vd, T, kv_frames=kvf, q_frames=qf)
+        dq, dk, dv = a.backward(qd, kd, vd, out, gd, lse, T, kv_frames=kvf, q_frames=qf)
+        dq2, dk2, dv2 = a.backward(qd, kd, vd, out, gd, lse, T, kv_frames=kvf, q_frames=qf)
+        torch.cuda.synchronize()
+    finally:
+        a.close()
+    assert torch.equal(dq, dq2) and torch.equal(dk, dk2) and torch.equal(dv, dv2)
+    rdq, rdk, rdv, rlse = orc.block_causal_attn_bwd(q, np.nan_to_num(k), np.nan_to_num(v), g, T, kv_frames=kvf,
+                                                    q_frames=qf)
+    Sk = kvf * T
+    tag = "general bwd %s T%d D%d" % (dtype, T, D)
+    for name, got, ref in (("dq", dq, rdq), ("dk", dk[:, :, :Sk], rdk[:, :, :Sk]), ("dv", dv[:, :, :Sk], rdv[:, :, :Sk])):
+        got = _host(got)
+        if dtype == "fp32":
+            err = float(np.abs(got - ref).max())
+            print("%s %s: max_abs=%.3e" % (tag, name, err), flush=True)
+            assert np.all(np.isfinite(got)) and err <= 1e-4, (tag, name, err)
+        else:
+            _check(got, ref, tag + " " + name)
+    assert float(dk[:, :, Sk:].abs().max() if F > kvf else 0.0) == 0.0
+    assert np.abs(lse.cpu().numpy() - rlse).max() <= (1e-5 if dtype == "fp32" else 2e-4)
