@@ -38,6 +38,9 @@ def main():
                     help="also time the training step of the attention: forward with log-sum-exp + backward (stderr and 'backward')")
     ap.add_argument("--rope", action="store_true",
                     help="also time the fused 3D rotary embedding + cache write on the workload's new frames (stderr and 'pre_op')")
+    ap.add_argument("--fp8kv", action="store_true",
+                    help="also time the cached workloads over the 8-bit (E4M3) KV cache: quantising append + forward "
+                         "(stderr and 'fp8_kv_cache')")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a 1 GiB device copy a few times (a kernel of known HBM bytes, for scaling profiler counters)")
     args = ap.parse_args()
@@ -56,7 +59,7 @@ def main():
     torch.cuda.set_device(0)
     attn = nb.Attention("bf16")
 
-    def time_workload(name, steps, warmup):
+    def time_workload(name, steps, warmup, kv8=False):
         cfg = wl.CONFIGS[name] if name in wl.CONFIGS else wl.EXTRA_CONFIGS[name]
         B, H, D, T, kvf, qf, F = (cfg[x] for x in ("B", "H", "D", "T", "kv_frames", "q_frames", "F"))
         # cached forms run "cold": every step takes the next of --cache-sets distinct K/V caches (one per layer of
@@ -66,14 +69,29 @@ def main():
         mk = lambda *s: torch.randn(*s, device="cuda", generator=gen, dtype=torch.float32).to(torch.bfloat16)
         cached = qf < kvf
         sets = []
+        if kv8:  # the same step over the 8-bit cache: quantising append of the new frames, then the forward
+            nbytes = nb.nfd_fp8_cache_bytes(B, H, F, T, D)
+            ksc = torch.full((B, H), 6.0 / 448.0, device="cuda")  # 6 sigma of N(0,1) at the top of the E4M3 range
+            vsc = torch.full((B, H), 6.0 / 448.0, device="cuda")
         for _ in range(rotate):
-            q, k, v = mk(B, H, qf * T, D), mk(B, H, F * T, D), mk(B, H, F * T, D)
-            kn = k[:, :, (kvf - qf) * T: kvf * T].clone() if cached else None
-            vn = v[:, :, (kvf - qf) * T: kvf * T].clone() if cached else None
+            q = mk(B, H, qf * T, D)
+            if kv8:
+                k, v = torch.zeros(nbytes, dtype=torch.uint8, device="cuda"), torch.zeros(nbytes, dtype=torch.uint8, device="cuda")
+                kn, vn = mk(B, H, kvf * T, D), mk(B, H, kvf * T, D)
+                nb.nfd_kvcache_append_fp8(attn.h, k, v, ksc, vsc, kn, vn, B, H, F, T, D, 0, kvf)
+                kn, vn = kn[:, :, (kvf - qf) * T:].clone(), vn[:, :, (kvf - qf) * T:].clone()
+            else:
+                k, v = mk(B, H, F * T, D), mk(B, H, F * T, D)
+                kn = k[:, :, (kvf - qf) * T: kvf * T].clone() if cached else None
+                vn = v[:, :, (kvf - qf) * T: kvf * T].clone() if cached else None
             sets.append((q, k, v, torch.empty_like(q), kn, vn))
 
         def step(i):
             q, k, v, out, kn, vn = sets[i % rotate]
+            if kv8:
+                nb.nfd_kvcache_append_fp8(attn.h, k, v, ksc, vsc, kn, vn, B, H, F, T, D, kvf - qf, qf)
+                nb.nfd_block_causal_attn_fwd_fp8kv(attn.h, q, k, v, ksc, vsc, out, B, H, F, T, D, kvf, qf)
+                return
             if cached:
                 nb.nfd_kvcache_append(attn.h, k, v, kn, vn, B, H, F, T, D, kvf - qf, qf)
             nb.nfd_block_causal_attn_fwd(attn.h, q, k, v, out, B, H, F, T, D, kvf, qf)
@@ -237,6 +255,18 @@ def main():
             others.append(r)
             print(json.dumps(r), file=sys.stderr, flush=True)
 
+    fp8kv = []
+    if args.fp8kv:
+        for name in wl.CONFIGS:
+            c = wl.CONFIGS[name]
+            if c["dtype"] != "bf16" or c["q_frames"] == c["kv_frames"]:
+                continue
+            r = time_workload(name, 200, 10, kv8=True)
+            r.pop("cfg")
+            fp8kv.append({k: (round(v, 4) if isinstance(v, float) else v) for k, v in r.items()
+                          if k in ("workload", "ms_per_step", "ms_median", "ms_min", "tflops", "frames_per_s")})
+            print(json.dumps({"fp8_kv_cache": fp8kv[-1]}), file=sys.stderr, flush=True)
+
     cpu = None
     if not args.no_cpu_baseline:
         from oracle import nfd_oracle as orc
@@ -297,6 +327,8 @@ def main():
         line["backward"] = backward
     if pre_op:
         line["pre_op"] = pre_op
+    if fp8kv:
+        line["fp8_kv_cache"] = fp8kv
     if others:
         line["other_workloads"] = [{k: (round(v, 4) if isinstance(v, float) else v) for k, v in r.items()
                                     if k in ("workload", "ms_per_step", "ms_median", "ms_min", "tflops", "gbs", "frames_per_s")} for r in others]

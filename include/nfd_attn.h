@@ -244,6 +244,41 @@ typedef struct nfd_attn_plan {
 int nfd_attn_plan(nfd_dtype_t dtype, int B, int H, int F, int T, int D, int kv_frames,
                   int q_frames, int num_cus, size_t workspace_limit, nfd_attn_plan_t* plan);
 
+/*
+ * 8-bit KV cache.  Appendix B's cache held as OCP E4M3 codes (1 sign, 4 exponent, 3 mantissa bits, bias 7,
+ * largest value 448): the post-training quantisation that Sec. 6 names as a further acceleration and leaves
+ * out.  The paper fixes no format; this one keeps the attention arithmetic unchanged: one scale per
+ * (batch, head) and tensor, supplied by the caller; code = E4M3(x / scale), nearest-even, saturating at
+ * +-448, x / scale formed as x * (1 / scale) in fp32; value read = code * scale.  The attention kernel
+ * widens the codes to bf16 (exact) on their way into the matrix cores and applies the scales to the softmax
+ * scale (K) and to the final result (V).
+ * Layouts (device memory, 16-byte aligned, owned by the caller):
+ *   k8  : [B, H, Spad, D] codes          v8t : [B, H, D, Spad] codes (feature-major)
+ *   Spad = F * T rounded up to a multiple of 64;  nfd_fp8_cache_bytes returns the size of EACH cache.
+ *   k_scale, v_scale : [B, H] fp32, positive.
+ * Codes outside the first kv_frames * T keys are never used, whatever they are.  Supported: bf16 handle, D = 64.
+ */
+int nfd_fp8_cache_bytes(int B, int H, int F, int T, int D, size_t* bytes);
+
+/* Quantise n_frames new frames (k_new, v_new: [B, H, n_frames*T, D] bf16) into frames frame_pos.. of the 8-bit
+ * caches.  Errors as nfd_kvcache_append, plus NFD_ERR_UNSUPPORTED for fp32 handles, D != 64 or misaligned
+ * tensors. */
+int nfd_kvcache_append_fp8(nfd_attn_t* h, void* k8, void* v8t, const float* k_scale, const float* v_scale,
+                           const void* k_new, const void* v_new, int B, int H, int F, int T, int D, int frame_pos,
+                           int n_frames, void* stream);
+
+/* nfd_kvcache_shift for the 8-bit caches: frames n_drop .. kv_frames-1 move to frames 0 .. ; same strategies
+ * and errors (NFD_ERR_UNSUPPORTED for D != 64).  Vector copies when n_drop * T is a multiple of 16, single
+ * bytes otherwise. */
+int nfd_kvcache_shift_fp8(nfd_attn_t* h, void* k8, void* v8t, int B, int H, int F, int T, int D, int kv_frames,
+                          int n_drop, void* stream);
+
+/* nfd_block_causal_attn_fwd with K and V read from the 8-bit caches; q and out are bf16.  Same schedule,
+ * key splits and errors; NFD_ERR_UNSUPPORTED for fp32 handles or D != 64. */
+int nfd_block_causal_attn_fwd_fp8kv(nfd_attn_t* h, const void* q, const void* k8, const void* v8t,
+                                    const float* k_scale, const float* v_scale, void* out, int B, int H, int F,
+                                    int T, int D, int kv_frames, int q_frames, float scale, void* stream);
+
 /* Which (head, query tile, key split) workgroup `block` of the matrix-core forward launch works on: the
  * same function the kernel evaluates, exposed so that the schedule can be checked without a GPU (every item
  * exactly once over blocks 0 .. n_workgroups-1).  group_q_tiles: the ordering used when K/V exceed the

@@ -27,6 +27,7 @@ EXPORTS = (
     "nfd_rope_kvcache_append", "nfd_rope_check_args",
     "nfd_block_causal_attn_fwd_lse", "nfd_block_causal_attn_bwd",
     "nfd_kvcache_shift", "nfd_spec_init", "nfd_spec_next", "nfd_spec_accept", "nfd_attn_work_item",
+    "nfd_fp8_cache_bytes", "nfd_kvcache_append_fp8", "nfd_block_causal_attn_fwd_fp8kv", "nfd_kvcache_shift_fp8",
 )
 
 
@@ -106,6 +107,14 @@ def lib():
         L.nfd_attn_plan.restype = ci
         L.nfd_attn_work_item.argtypes = [ci] * 4 + [ctypes.c_uint] + [ctypes.POINTER(ci)] * 3
         L.nfd_attn_work_item.restype = ci
+        L.nfd_fp8_cache_bytes.argtypes = [ci] * 5 + [ctypes.POINTER(ctypes.c_size_t)]
+        L.nfd_fp8_cache_bytes.restype = ci
+        L.nfd_kvcache_append_fp8.argtypes = [vp] * 7 + [ci] * 7 + [vp]
+        L.nfd_kvcache_append_fp8.restype = ci
+        L.nfd_kvcache_shift_fp8.argtypes = [vp, vp, vp] + [ci] * 7 + [vp]
+        L.nfd_kvcache_shift_fp8.restype = ci
+        L.nfd_block_causal_attn_fwd_fp8kv.argtypes = [vp] * 7 + [ci] * 7 + [cf, vp]
+        L.nfd_block_causal_attn_fwd_fp8kv.restype = ci
         L.nfd_attn_visible_pairs.argtypes = [ci] * 3
         L.nfd_attn_visible_pairs.restype = ctypes.c_int64
         _lib = L
@@ -184,6 +193,31 @@ def nfd_rope_check_args(dtype, B, H, F, T, D, frame_pos, n_frames, grid_h, grid_
 def nfd_kvcache_shift(h, k_cache, v_cache, B, H, F, T, D, kv_frames, n_drop, stream=None):
     rc = lib().nfd_kvcache_shift(h, _addr(k_cache), _addr(v_cache), B, H, F, T, D, kv_frames, n_drop, _stream(stream))
     _check(rc, "nfd_kvcache_shift", h)
+
+
+def nfd_fp8_cache_bytes(B, H, F, T, D):
+    """Bytes of each of the two 8-bit caches (K codes and feature-major V codes)."""
+    n = ctypes.c_size_t(0)
+    _check(lib().nfd_fp8_cache_bytes(B, H, F, T, D, ctypes.byref(n)), "nfd_fp8_cache_bytes")
+    return n.value
+
+
+def nfd_kvcache_append_fp8(h, k8, v8t, k_scale, v_scale, k_new, v_new, B, H, F, T, D, frame_pos, n_frames, stream=None):
+    rc = lib().nfd_kvcache_append_fp8(h, _addr(k8), _addr(v8t), _addr(k_scale), _addr(v_scale), _addr(k_new),
+                                      _addr(v_new), B, H, F, T, D, frame_pos, n_frames, _stream(stream))
+    _check(rc, "nfd_kvcache_append_fp8", h)
+
+
+def nfd_kvcache_shift_fp8(h, k8, v8t, B, H, F, T, D, kv_frames, n_drop, stream=None):
+    rc = lib().nfd_kvcache_shift_fp8(h, _addr(k8), _addr(v8t), B, H, F, T, D, kv_frames, n_drop, _stream(stream))
+    _check(rc, "nfd_kvcache_shift_fp8", h)
+
+
+def nfd_block_causal_attn_fwd_fp8kv(h, q, k8, v8t, k_scale, v_scale, out, B, H, F, T, D, kv_frames, q_frames,
+                                    scale=0.0, stream=None):
+    rc = lib().nfd_block_causal_attn_fwd_fp8kv(h, _addr(q), _addr(k8), _addr(v8t), _addr(k_scale), _addr(v_scale),
+                                               _addr(out), B, H, F, T, D, kv_frames, q_frames, scale, _stream(stream))
+    _check(rc, "nfd_block_causal_attn_fwd_fp8kv", h)
 
 
 def nfd_spec_init(capacity, window, n_spec, n_prompt, total):

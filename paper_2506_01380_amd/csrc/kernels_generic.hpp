@@ -252,7 +252,8 @@ attn_bwd_dkdv_generic(BwdGenericParams p) {
 // otherwise one tensor element): head_dst / head_src = head strides, off_dst / off_src = offsets
 // inside a head, len = units per head.  blockIdx.y walks over the heads, blockIdx.x over the units of a
 // head, so no thread divides.
-template <typename E>
+// PAIR = false: one tensor only (kd, ks); vd and vs are not touched.
+template <typename E, bool PAIR = true>
 __global__ void __launch_bounds__(256)
 kvcache_copy(E* __restrict__ kd, E* __restrict__ vd, const E* __restrict__ ks, const E* __restrict__ vs,
              int64_t head_dst, int64_t head_src, int64_t off_dst, int64_t off_src, int64_t len, int64_t heads) {
@@ -260,7 +261,7 @@ kvcache_copy(E* __restrict__ kd, E* __restrict__ vd, const E* __restrict__ ks, c
         const int64_t dbase = bh * head_dst + off_dst, sbase = bh * head_src + off_src;
         for (int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; r < len; r += (int64_t)gridDim.x * blockDim.x) {
             kd[dbase + r] = ks[sbase + r];
-            vd[dbase + r] = vs[sbase + r];
+            if constexpr (PAIR) vd[dbase + r] = vs[sbase + r];
         }
     }
 }

@@ -30,6 +30,8 @@
 // bound of the workgroup (of the wavefront) are never visited (computed); only the tiles in
 // between compare the key index with the lane's bound.
 #pragma once
+#include <type_traits>
+
 #include "nfd_common.hpp"
 
 namespace nfd {
@@ -70,6 +72,27 @@ struct __attribute__((aligned(16))) SmemRing {
     __bf16 k[kRingSlots][kTileElems];
     __bf16 v[kRingSlots][kTileElems];
 };
+
+// 8-bit cache (E4M3 codes): a K tile is 64 keys x 64 features, a V tile 64 features x 64 keys (V is stored
+// feature-major), both 64 rows of 64 bytes.  One wave instruction of 16-byte loads fills 16 tile rows, so a tile
+// is one load per wavefront and tensor.  The 16-byte chunk c of row r sits at chunk position c ^ ((r >> 2) & 3):
+// the 16-byte fragment reads of 16 consecutive rows (one chunk each) then cover all 64 banks exactly once.
+struct __attribute__((aligned(16))) SmemRing8 {
+    unsigned char k[kRingSlots][kTileElems];
+    unsigned char v[kRingSlots][kTileElems];
+};
+__device__ __forceinline__ int chunk_swizzle8(int r) { return (r >> 2) & 3; }
+
+// Eight E4M3 codes (two dwords, lowest byte first) widened to bf16; every E4M3 value is a bf16 value.
+__device__ __forceinline__ bf16x8 widen_e4m3x8(uint32_t w0, uint32_t w1) {
+    const bf16x2 a = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w0, 1.0f, false);
+    const bf16x2 b = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w0, 1.0f, true);
+    const bf16x2 c = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w1, 1.0f, false);
+    const bf16x2 d = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w1, 1.0f, true);
+    const bf16x4 ab = __builtin_shufflevector(a, b, 0, 1, 2, 3);
+    const bf16x4 cd = __builtin_shufflevector(c, d, 0, 1, 2, 3);
+    return __builtin_shufflevector(ab, cd, 0, 1, 2, 3, 4, 5, 6, 7);
+}
 
 // Work decomposition of one launch.  Workgroup ids are dealt round-robin to the 8 XCDs.
 // When the head count is a multiple of 8, heads are pinned to an XCD (bh % 8) so that all query
@@ -160,13 +183,18 @@ __device__ __forceinline__ void store_rows(const FwdParams& p, const WorkItem& w
 // QT = 1: 32 rows per wavefront, 128 per workgroup, three wavefronts per SIMD: half the softmax and half the
 // matrix work per tile and wavefront, i.e. a shorter chain per key tile, for calls with few query rows whose
 // time is the length of that chain (cached forms); it reads twice the LDS bytes per FLOP.
-template <int QT>
+//
+// KV8: K and V come from the 8-bit cache (see SmemRing8) and are widened to bf16 on their way from LDS into
+// the matrix operands; the per-head scales are folded into the softmax scale (K) and the final write (V), so
+// the arithmetic between the operands is the same as for a bf16 cache.  The feature order inside the first
+// product's contraction is permuted (a 16-byte read serves two steps), the same way for K and Q.
+template <int QT, bool KV8 = false>
 __global__ void __launch_bounds__(kWaves * 64, QT == 2 ? 2 : 3)
 attn_fwd_bf16_d64(FwdParams p) {
     constexpr int BM = kWaves * 32 * QT;
     constexpr int WR = 32 * QT;  // query rows per wavefront
     constexpr int PRIO = kMfmaPriority;
-    __shared__ SmemRing sm;
+    __shared__ typename std::conditional<KV8, SmemRing8, SmemRing>::type sm;
     const WorkItem wi = decode_work(p);
     if (!wi.valid) return;  // whole workgroup leaves together
 
@@ -195,7 +223,12 @@ attn_fwd_bf16_d64(FwdParams p) {
         const int rc = min(row[qt], p.Sq - 1);  // ragged tail: compute a duplicate, never store it
         kmax_lane[qt] = kmax_of_row(rc, p.T, p.P);
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks) qf[qt][ks] = *(const bf16x8*)(qg + (int64_t)rc * kD + 16 * ks + 8 * h);
+        for (int ks = 0; ks < 4; ++ks) {
+            // contraction step ks, lane half h: features 16*ks + 8*h ..+7; with the 8-bit cache the features of
+            // the 16-byte chunk 2*(ks/2) + h, first or second half (ks % 2) - the order the K reads deliver
+            const int d0 = KV8 ? 16 * (2 * (ks >> 1) + h) + 8 * (ks & 1) : 16 * ks + 8 * h;
+            qf[qt][ks] = *(const bf16x8*)(qg + (int64_t)rc * kD + d0);
+        }
     }
     const int rw_first = min(rw0, p.Sq - 1), rw_last = min(rw0 + WR - 1, p.Sq - 1);
     const int kmin_wave = kmax_of_row(rw_first, p.T, p.P);  // tiles ending at or below need no mask
@@ -213,7 +246,8 @@ attn_fwd_bf16_d64(FwdParams p) {
     float l_sum[QT];   // this lane's share of the row sum
 #pragma unroll
     for (int qt = 0; qt < QT; ++qt) { m_used[qt] = kNegBig; l_sum[qt] = 0.f; }
-    const float c = p.scale_log2e;
+    float c = p.scale_log2e;
+    if constexpr (KV8) c *= p.k_scale[wi.bh];  // scores of the codes -> scores of the values
 
     // ---- tile loads: one wave instruction fills 8 consecutive tile rows (1 KB); a wavefront owns
     // rows 8*wave + 32*pass + lane/8, and each lane fetches the chunk that belongs at its position ----
@@ -221,7 +255,20 @@ attn_fwd_bf16_d64(FwdParams p) {
     const int ld_chunk = (lane & 7) ^ chunk_swizzle(ld_row);  // rows +32: same swizzle
     const unsigned lds_k0 = (unsigned)(size_t)(__attribute__((address_space(3))) char*)(&sm.k[0][0]) + wave * 1024;
     const unsigned lds_v0 = (unsigned)(size_t)(__attribute__((address_space(3))) char*)(&sm.v[0][0]) + wave * 1024;
+    // 8-bit cache: one instruction fills 16 tile rows of 64 bytes; the tensors are padded to whole tiles, so no
+    // row is clamped (codes past the end are masked: K by the score mask, V explicitly in the last tile)
+    const int ld_row8 = 16 * wave + (lane >> 2);
+    const int64_t ld_chunk8 = 16 * ((lane & 3) ^ chunk_swizzle8(ld_row8));
+    const unsigned char* k_src8 = (const unsigned char*)p.k + ((int64_t)wi.bh * p.Spad + ld_row8) * kD + ld_chunk8;
+    const unsigned char* v_src8 = (const unsigned char*)p.v + ((int64_t)wi.bh * kD + ld_row8) * p.Spad + ld_chunk8;
     auto load_tile = [&](int t, int slot) {  // rows past the end are clamped: they are masked anyway
+        if constexpr (KV8) {
+            const unsigned kdst = lds_k0 + (unsigned)(slot * kTileElems);
+            const unsigned vdst = lds_v0 + (unsigned)(slot * kTileElems);
+            asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(k_src8 + (int64_t)t * kBN * kD), "s"(kdst) : "memory", "m0");
+            asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(v_src8 + (int64_t)t * kBN), "s"(vdst) : "memory", "m0");
+            return;
+        }
         // Issued through inline assembly on purpose: for the builtin the compiler guards every later
         // LDS read and every barrier with vmcnt(0), which would cancel the prefetch distance.  The
         // waits that order these loads are the explicit ones at the top of the tile loop.
@@ -251,6 +298,15 @@ attn_fwd_bf16_d64(FwdParams p) {
 #pragma unroll
         for (int sec = 0; sec < 2; ++sec)
             v_off[dt][sec] = (v_row + 8 * sec) * kD + 8 * ((4 * dt + v_chunk) ^ (fv ^ (2 * sec))) + 4 * (s16 & 1);
+    // 8-bit cache, byte offsets.  K: lane (n, h) reads chunk 2*kp + h of key row 32*kb + n (the swizzle of a row
+    // does not depend on kb): 16 features = two contraction steps.  V: lane (n, h) reads, of feature row
+    // 32*dt + n, the keys 4h..4h+3 and 8+4h..8+4h+3 of the 16-key chunk 2*kb + g: the rows of P it multiplies.
+    const int f8 = chunk_swizzle8(n);
+    int k_off8[2], v_off8[4];
+#pragma unroll
+    for (int kp = 0; kp < 2; ++kp) k_off8[kp] = n * kD + 16 * ((2 * kp + h) ^ f8);
+#pragma unroll
+    for (int ch = 0; ch < 4; ++ch) v_off8[ch] = n * kBN + 16 * (ch ^ f8) + 4 * h;
 
     if (t_begin < t_end) load_tile(t_begin, 0);
     if (t_begin + 1 < t_end) load_tile(t_begin + 1, 1);
@@ -261,15 +317,30 @@ attn_fwd_bf16_d64(FwdParams p) {
     auto compute_tile = [&](int t, int slot) {
         const int j0 = t * kBN;
         if (wave_active && j0 < kmax_wave) {
-            const __bf16* ks_ = sm.k[slot];
-            const __bf16* vs_ = sm.v[slot];
+            const auto* ks_ = sm.k[slot];
+            const auto* vs_ = sm.v[slot];
             // ---- S^T = K . Q^T: all eight K fragments are requested before the first product ------
             f32x16 s_acc[2][QT];  // [kb][qt]
             bf16x8 kf[2][4];
+            if constexpr (KV8) {
+                u32x4 raw[2][2];
 #pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
+                for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-                for (int ks = 0; ks < 4; ++ks) kf[kb][ks] = lds_read_b128(ks_ + 32 * kb * kD + k_off[ks]);
+                    for (int kp = 0; kp < 2; ++kp) raw[kb][kp] = *(const u32x4*)(ks_ + 32 * kb * kD + k_off8[kp]);
+#pragma unroll
+                for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                    for (int kp = 0; kp < 2; ++kp) {
+                        kf[kb][2 * kp] = widen_e4m3x8(raw[kb][kp][0], raw[kb][kp][1]);
+                        kf[kb][2 * kp + 1] = widen_e4m3x8(raw[kb][kp][2], raw[kb][kp][3]);
+                    }
+            } else {
+#pragma unroll
+                for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                    for (int ks = 0; ks < 4; ++ks) kf[kb][ks] = lds_read_b128(ks_ + 32 * kb * kD + k_off[ks]);
+            }
             __builtin_amdgcn_sched_barrier(0);
             // Raised priority from here to the end of the K.Q^T run, and again from the P.V run to
             // this point of the next tile: when the two wavefronts of a SIMD are in different
@@ -298,7 +369,18 @@ attn_fwd_bf16_d64(FwdParams p) {
                     for (int g = 0; g < 2; ++g)
 #pragma unroll
                         for (int dt = 0; dt < 2; ++dt) {
-                            const __bf16* vp = vs_ + (32 * kb + 16 * g) * kD;
+                            if constexpr (KV8) {
+                                const uint32_t* vp8 = (const uint32_t*)(vs_ + 32 * dt * kBN + v_off8[2 * kb + g]);
+                                uint32_t w0 = vp8[0], w1 = vp8[2];
+                                if (j0 + kBN > p.Sk) {  // last tile of the cache: codes past the end count as zero
+                                    const int left = p.Sk - (j0 + 32 * kb + 16 * g + 4 * h);  // keys left from w0's first
+                                    w0 = left >= 4 ? w0 : left <= 0 ? 0u : w0 & ((1u << (8 * left)) - 1u);
+                                    w1 = left >= 12 ? w1 : left <= 8 ? 0u : w1 & ((1u << (8 * (left - 8))) - 1u);
+                                }
+                                vf[kb][g][dt] = widen_e4m3x8(w0, w1);
+                                continue;
+                            }
+                            const __bf16* vp = (const __bf16*)vs_ + (32 * kb + 16 * g) * kD;
                             const s16x4 lo = lds_read_tr(vp + v_off[dt][0]);
                             const s16x4 hi = lds_read_tr(vp + v_off[dt][1]);
                             typedef __attribute__((ext_vector_type(8))) short s16x8;
@@ -406,8 +488,12 @@ attn_fwd_bf16_d64(FwdParams p) {
         // after the barrier it has landed for all, and every wavefront is done with tile t-1, whose
         // slot the load of tile t+2 reuses.
         __builtin_amdgcn_sched_barrier(0);
-        if (t + 1 < t_end) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
-        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        if (t + 1 < t_end) {  // all but the next tile's loads of this wavefront (four; two with the 8-bit cache)
+            if constexpr (KV8) asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
+            else asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+        } else {
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        }
         __builtin_amdgcn_s_barrier();
         __builtin_amdgcn_sched_barrier(0);
         const int slot2 = slot == 0 ? 2 : slot - 1;  // (slot + 2) % 3
@@ -417,6 +503,15 @@ attn_fwd_bf16_d64(FwdParams p) {
     }
 
     if (!wave_active) return;
+    if constexpr (KV8) {  // values of V = codes * scale: linear, so applied once to the accumulator
+        const float vs = p.v_scale[wi.bh];
+#pragma unroll
+        for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+            for (int qt = 0; qt < QT; ++qt)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) o_acc[dt][qt][r] *= vs;
+    }
     store_rows<QT>(p, wi, row, h, o_acc, l_sum, m_used, c);
 }
 

@@ -13,6 +13,7 @@
 #include <new>
 #include <string>
 
+#include "kernels_fp8.hpp"
 #include "kernels_generic.hpp"
 #include "kernels_mfma.hpp"
 #include "kernels_mfma_bwd.hpp"
@@ -219,10 +220,13 @@ int nfd_attn_destroy(nfd_attn_t* h) {
 
 const char* nfd_last_error(const nfd_attn_t* h) { return h ? h->err.c_str() : "null handle"; }
 
+// k_scale / v_scale non-null: k and v are the 8-bit caches (see nfd_kvcache_append_fp8).
 static int fwd_impl(nfd_attn_t* h, const void* q, const void* k, const void* v, void* out, float* lse, int B,
-                    int H, int F, int T, int D, int kv_frames, int q_frames, float scale, void* stream) {
+                    int H, int F, int T, int D, int kv_frames, int q_frames, float scale, void* stream,
+                    const float* k_scale = nullptr, const float* v_scale = nullptr) {
     if (!h) return NFD_ERR_NULL;
     if (!q || !k || !v || !out) return fail(h, NFD_ERR_NULL, "q, k, v and out must be non-null");
+    const bool kv8 = k_scale != nullptr;
     nfd_attn_plan_t pl;
     const int rc = nfd_attn_plan(h->dtype, B, H, F, T, D, kv_frames, q_frames, h->num_cus, h->workspace_bytes, &pl);
     if (rc != NFD_OK) return fail(h, rc, "invalid shape arguments");
@@ -232,9 +236,12 @@ static int fwd_impl(nfd_attn_t* h, const void* q, const void* k, const void* v, 
     // The matrix-core kernels move 16-byte vectors; a view that starts in the middle of a vector would fault.
     if (pl.kernel == 1 && (((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)out) % 16 != 0 || (uintptr_t)lse % 4 != 0))
         return fail(h, NFD_ERR_UNSUPPORTED, "q, k, v, out must be 16-byte aligned (lse 4-byte)");
+    if (kv8 && pl.kernel != 1) return fail(h, NFD_ERR_UNSUPPORTED, "the 8-bit cache is built for bf16 queries and head width 64");
     if (!(scale > 0.f)) scale = 1.0f / std::sqrt((float)D);
 
     nfd::FwdParams p{};
+    p.k_scale = k_scale; p.v_scale = v_scale;
+    p.Spad = (int)(((int64_t)F * T + 63) / 64 * 64);
     p.q = q; p.k = k; p.v = v; p.out = out;
     p.lse = lse;
     p.BH = B * H;
@@ -247,7 +254,7 @@ static int fwd_impl(nfd_attn_t* h, const void* q, const void* k, const void* v, 
     p.n_q_tiles = pl.n_q_tiles;
     p.n_splits = pl.n_splits;
     // K and V of all heads against the 256 MB last-level cache (with room for Q, O and partials)
-    p.group_q_tiles = pl.n_splits > 1 && (double)p.BH * p.Sk * nfd::mfma::kD * 2.0 * 2.0 > 192e6;
+    p.group_q_tiles = pl.n_splits > 1 && (double)p.BH * p.Sk * nfd::mfma::kD * 2.0 * (kv8 ? 1.0 : 2.0) > 192e6;
     p.scale_log2e = scale * nfd::kLog2e;
     if (pl.n_splits > 1) {
         p.part_o = (float*)h->workspace;
@@ -256,10 +263,15 @@ static int fwd_impl(nfd_attn_t* h, const void* q, const void* k, const void* v, 
     hipStream_t st = (hipStream_t)stream;
 
     if (pl.kernel == 1) {
-        if (pl.block_m == nfd::mfma::kBM)
-            hipLaunchKernelGGL(nfd::mfma::attn_fwd_bf16_d64<2>, dim3(pl.n_workgroups), dim3(nfd::mfma::kWaves * 64), 0, st, p);
+        const dim3 grid(pl.n_workgroups), block(nfd::mfma::kWaves * 64);
+        if (kv8 && pl.block_m == nfd::mfma::kBM)
+            hipLaunchKernelGGL((nfd::mfma::attn_fwd_bf16_d64<2, true>), grid, block, 0, st, p);
+        else if (kv8)
+            hipLaunchKernelGGL((nfd::mfma::attn_fwd_bf16_d64<1, true>), grid, block, 0, st, p);
+        else if (pl.block_m == nfd::mfma::kBM)
+            hipLaunchKernelGGL((nfd::mfma::attn_fwd_bf16_d64<2, false>), grid, block, 0, st, p);
         else
-            hipLaunchKernelGGL(nfd::mfma::attn_fwd_bf16_d64<1>, dim3(pl.n_workgroups), dim3(nfd::mfma::kWaves * 64), 0, st, p);
+            hipLaunchKernelGGL((nfd::mfma::attn_fwd_bf16_d64<1, false>), grid, block, 0, st, p);
         if (pl.n_splits > 1) {
             const int64_t total = (int64_t)p.BH * p.Sq * (nfd::mfma::kD / 4);
             hipLaunchKernelGGL(nfd::mfma::attn_combine_d64, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, p);
@@ -283,6 +295,54 @@ int nfd_block_causal_attn_fwd_lse(nfd_attn_t* h, const void* q, const void* k, c
                                   float scale, void* stream) {
     if (h && !lse) return fail(h, NFD_ERR_NULL, "lse must be non-null");
     return fwd_impl(h, q, k, v, out, lse, B, H, F, T, D, kv_frames, q_frames, scale, stream);
+}
+
+int nfd_fp8_cache_bytes(int B, int H, int F, int T, int D, size_t* bytes) {
+    if (!bytes) return NFD_ERR_NULL;
+    if (B < 1 || H < 1 || F < 1 || T < 1 || D < 1) return NFD_ERR_SHAPE;
+    if (D != nfd::mfma::kD) return NFD_ERR_UNSUPPORTED;
+    if ((int64_t)F * T > (int64_t)1 << 30 || (int64_t)B * H > (int64_t)1 << 24) return NFD_ERR_UNSUPPORTED;
+    const int64_t Spad = ((int64_t)F * T + 63) / 64 * 64;
+    *bytes = (size_t)B * H * Spad * D;
+    return NFD_OK;
+}
+
+int nfd_block_causal_attn_fwd_fp8kv(nfd_attn_t* h, const void* q, const void* k8, const void* v8t,
+                                    const float* k_scale, const float* v_scale, void* out, int B, int H, int F,
+                                    int T, int D, int kv_frames, int q_frames, float scale, void* stream) {
+    if (!h) return NFD_ERR_NULL;
+    if (!k_scale || !v_scale) return fail(h, NFD_ERR_NULL, "k_scale and v_scale must be non-null");
+    if ((uintptr_t)k_scale % 4 != 0 || (uintptr_t)v_scale % 4 != 0)
+        return fail(h, NFD_ERR_UNSUPPORTED, "scales must be 4-byte aligned");
+    return fwd_impl(h, q, k8, v8t, out, nullptr, B, H, F, T, D, kv_frames, q_frames, scale, stream, k_scale, v_scale);
+}
+
+int nfd_kvcache_append_fp8(nfd_attn_t* h, void* k8, void* v8t, const float* k_scale, const float* v_scale,
+                           const void* k_new, const void* v_new, int B, int H, int F, int T, int D, int frame_pos,
+                           int n_frames, void* stream) {
+    if (!h) return NFD_ERR_NULL;
+    if (!k8 || !v8t || !k_scale || !v_scale || !k_new || !v_new)
+        return fail(h, NFD_ERR_NULL, "caches, scales and new tensors must be non-null");
+    if (B < 1 || H < 1 || F < 1 || T < 1 || D < 1 || n_frames < 0 || frame_pos < 0)
+        return fail(h, NFD_ERR_SHAPE, "invalid shape arguments");
+    if ((int64_t)frame_pos + n_frames > F) return fail(h, NFD_ERR_CAPACITY, "frame_pos + n_frames exceeds the cache capacity F");
+    if (h->dtype != NFD_BF16 || D != nfd::mfma::kD)
+        return fail(h, NFD_ERR_UNSUPPORTED, "the 8-bit cache is built for bf16 inputs and head width 64");
+    if ((int64_t)F * T > (int64_t)1 << 30 || (int64_t)B * H > (int64_t)1 << 24)
+        return fail(h, NFD_ERR_UNSUPPORTED, "shape beyond the 32-bit row indexing of the kernels");
+    if (((uintptr_t)k8 | (uintptr_t)v8t | (uintptr_t)k_new | (uintptr_t)v_new) % 16 != 0 ||
+        ((uintptr_t)k_scale | (uintptr_t)v_scale) % 4 != 0)
+        return fail(h, NFD_ERR_UNSUPPORTED, "caches and new tensors must be 16-byte aligned (scales 4-byte)");
+    if (n_frames == 0) return NFD_OK;
+    const int n_rows = n_frames * T, j0 = frame_pos * T, BH = B * H;
+    const int64_t Spad = ((int64_t)F * T + 63) / 64 * 64;
+    hipStream_t st = (hipStream_t)stream;
+    const unsigned gy = (unsigned)std::min(BH, 65535);
+    const unsigned k_blocks = (unsigned)(((int64_t)n_rows * 8 + 255) / 256), v_blocks = (unsigned)((n_rows + 63) / 64);
+    hipLaunchKernelGGL(nfd::kvcache_append_fp8, dim3(k_blocks + v_blocks, gy), dim3(256), 0, st, (const __bf16*)k_new,
+                       (const __bf16*)v_new, (unsigned char*)k8, (unsigned char*)v8t, k_scale, v_scale, n_rows, Spad, j0,
+                       BH, k_blocks);
+    return check_hip(h, hipGetLastError(), "8-bit kvcache append launch");
 }
 
 int nfd_block_causal_attn_bwd(nfd_attn_t* h, const void* q, const void* k, const void* v, const void* out,
@@ -348,11 +408,12 @@ int nfd_block_causal_attn_bwd(nfd_attn_t* h, const void* q, const void* k, const
     return check_hip(h, hipGetLastError(), "backward launch");
 }
 
-// Launch one K+V frame-run copy (see kvcache_copy); all arguments in elements.
-static void launch_frame_copy(nfd_attn_t* h, void* kd, void* vd, const void* ks, const void* vs, int64_t BH,
+// Launch one frame-run copy (see kvcache_copy) of two tensors of equal geometry, or of one (vd == nullptr);
+// all counts in elements of es bytes.
+static void launch_frame_copy(nfd_attn_t* h, size_t es, void* kd, void* vd, const void* ks, const void* vs, int64_t BH,
                               int64_t head_dst, int64_t head_src, int64_t off_dst, int64_t off_src, int64_t len,
                               hipStream_t st) {
-    const size_t es = elem_size(h->dtype);
+    const bool pair = vd != nullptr;
     const bool vec = (head_dst * es) % 16 == 0 && (head_src * es) % 16 == 0 && (off_dst * es) % 16 == 0 &&
                      (off_src * es) % 16 == 0 && (len * es) % 16 == 0 && ((uintptr_t)kd % 16 == 0) &&
                      ((uintptr_t)vd % 16 == 0) && ((uintptr_t)ks % 16 == 0) && ((uintptr_t)vs % 16 == 0);
@@ -362,17 +423,44 @@ static void launch_frame_copy(nfd_attn_t* h, void* kd, void* vd, const void* ks,
         const int64_t want_x = std::max<int64_t>(1, ((int64_t)h->num_cus * 32 + gy - 1) / gy);  // enough blocks to fill the chip
         return dim3((unsigned)std::min<int64_t>((units + 255) / 256, want_x), (unsigned)gy);
     };
-    if (vec) {
-        const int64_t f = 16 / es;
-        hipLaunchKernelGGL(nfd::kvcache_copy<nfd::u32x4>, grid_for(len / f), block, 0, st, (nfd::u32x4*)kd, (nfd::u32x4*)vd,
-                           (const nfd::u32x4*)ks, (const nfd::u32x4*)vs, head_dst / f, head_src / f, off_dst / f,
-                           off_src / f, len / f, BH);
-    } else if (es == 2) {
-        hipLaunchKernelGGL(nfd::kvcache_copy<uint16_t>, grid_for(len), block, 0, st, (uint16_t*)kd, (uint16_t*)vd,
-                           (const uint16_t*)ks, (const uint16_t*)vs, head_dst, head_src, off_dst, off_src, len, BH);
+    auto go = [&](auto tag, int64_t f) {  // f = elements per unit of the copy type
+        typedef decltype(tag) E;
+        if (pair)
+            hipLaunchKernelGGL((nfd::kvcache_copy<E, true>), grid_for(len / f), block, 0, st, (E*)kd, (E*)vd, (const E*)ks,
+                               (const E*)vs, head_dst / f, head_src / f, off_dst / f, off_src / f, len / f, BH);
+        else
+            hipLaunchKernelGGL((nfd::kvcache_copy<E, false>), grid_for(len / f), block, 0, st, (E*)kd, (E*)nullptr,
+                               (const E*)ks, (const E*)nullptr, head_dst / f, head_src / f, off_dst / f, off_src / f,
+                               len / f, BH);
+    };
+    if (vec) go(nfd::u32x4{}, (int64_t)(16 / es));
+    else if (es == 1) go((unsigned char)0, 1);
+    else if (es == 2) go((uint16_t)0, 1);
+    else go((uint32_t)0, 1);
+}
+
+// Move frames n_drop .. kv_frames-1 of every head to frames 0 .. of the same tensors (two of equal geometry,
+// or one when b == nullptr): heads of head elements each, fe elements per frame, es bytes per element.
+static void shift_frames(nfd_attn_t* h, size_t es, void* a, void* b, int64_t heads, int64_t head, int64_t fe,
+                         int kv_frames, int n_drop, hipStream_t st) {
+    const int keep = kv_frames - n_drop;
+    const size_t half = ((size_t)(heads * keep * fe) * es + 255) / 256 * 256;  // staging bytes per tensor
+    if (keep <= n_drop) {
+        // source and destination frames are disjoint: one copy inside the tensors
+        launch_frame_copy(h, es, a, b, a, b, heads, head, head, 0, (int64_t)n_drop * fe, keep * fe, st);
+    } else if ((b ? 2 : 1) * half <= h->workspace_bytes) {
+        // overlapping ranges: through the workspace (out, then back)
+        void* as = h->workspace;
+        void* bs = b ? (char*)h->workspace + half : nullptr;
+        launch_frame_copy(h, es, as, bs, a, b, heads, keep * fe, head, 0, (int64_t)n_drop * fe, keep * fe, st);
+        launch_frame_copy(h, es, a, b, as, bs, heads, head, keep * fe, 0, 0, keep * fe, st);
     } else {
-        hipLaunchKernelGGL(nfd::kvcache_copy<uint32_t>, grid_for(len), block, 0, st, (uint32_t*)kd, (uint32_t*)vd,
-                           (const uint32_t*)ks, (const uint32_t*)vs, head_dst, head_src, off_dst, off_src, len, BH);
+        // workspace too small: runs of n_drop frames, oldest first; within a run source and destination are disjoint
+        for (int f = n_drop; f < kv_frames; f += n_drop) {
+            const int n = std::min(n_drop, kv_frames - f);
+            launch_frame_copy(h, es, a, b, a, b, heads, head, head, (int64_t)(f - n_drop) * fe, (int64_t)f * fe,
+                              (int64_t)n * fe, st);
+        }
     }
 }
 
@@ -385,7 +473,7 @@ int nfd_kvcache_append(nfd_attn_t* h, void* k_cache, void* v_cache, const void* 
     if ((int64_t)frame_pos + n_frames > F) return fail(h, NFD_ERR_CAPACITY, "frame_pos + n_frames exceeds the cache capacity F");
     if (n_frames == 0) return NFD_OK;
     const int64_t frame_elems = (int64_t)T * D;
-    launch_frame_copy(h, k_cache, v_cache, k_new, v_new, (int64_t)B * H, (int64_t)F * frame_elems,
+    launch_frame_copy(h, elem_size(h->dtype), k_cache, v_cache, k_new, v_new, (int64_t)B * H, (int64_t)F * frame_elems,
                       (int64_t)n_frames * frame_elems, (int64_t)frame_pos * frame_elems, 0,
                       (int64_t)n_frames * frame_elems, (hipStream_t)stream);
     return check_hip(h, hipGetLastError(), "kvcache append launch");
@@ -398,30 +486,30 @@ int nfd_kvcache_shift(nfd_attn_t* h, void* k_cache, void* v_cache, int B, int H,
     if (B < 1 || H < 1 || F < 1 || T < 1 || D < 1 || kv_frames < 0 || n_drop < 0 || n_drop > kv_frames)
         return fail(h, NFD_ERR_SHAPE, "invalid shape arguments");
     if (kv_frames > F) return fail(h, NFD_ERR_CAPACITY, "kv_frames exceeds the cache capacity F");
-    const int keep = kv_frames - n_drop;
-    if (n_drop == 0 || keep == 0) return NFD_OK;
-    const int64_t fe = (int64_t)T * D, BH = (int64_t)B * H, head = (int64_t)F * fe;
-    const size_t es = elem_size(h->dtype);
-    hipStream_t st = (hipStream_t)stream;
-    const size_t half = ((size_t)(BH * keep * fe) * es + 255) / 256 * 256;  // staging bytes per tensor
-    if (keep <= n_drop) {
-        // source and destination frames are disjoint: one copy inside the caches
-        launch_frame_copy(h, k_cache, v_cache, k_cache, v_cache, BH, head, head, 0, (int64_t)n_drop * fe, keep * fe, st);
-    } else if (2 * half <= h->workspace_bytes) {
-        // overlapping ranges: through the workspace (out, then back)
-        void* ks = h->workspace;
-        void* vs = (char*)h->workspace + half;
-        launch_frame_copy(h, ks, vs, k_cache, v_cache, BH, keep * fe, head, 0, (int64_t)n_drop * fe, keep * fe, st);
-        launch_frame_copy(h, k_cache, v_cache, ks, vs, BH, head, keep * fe, 0, 0, keep * fe, st);
-    } else {
-        // workspace too small: runs of n_drop frames, oldest first; within a run source and destination are disjoint
-        for (int f = n_drop; f < kv_frames; f += n_drop) {
-            const int n = std::min(n_drop, kv_frames - f);
-            launch_frame_copy(h, k_cache, v_cache, k_cache, v_cache, BH, head, head, (int64_t)(f - n_drop) * fe,
-                              (int64_t)f * fe, (int64_t)n * fe, st);
-        }
-    }
+    if (n_drop == 0 || kv_frames == n_drop) return NFD_OK;
+    shift_frames(h, elem_size(h->dtype), k_cache, v_cache, (int64_t)B * H, (int64_t)F * T * D, (int64_t)T * D, kv_frames,
+                 n_drop, (hipStream_t)stream);
     return check_hip(h, hipGetLastError(), "kvcache shift launch");
+}
+
+int nfd_kvcache_shift_fp8(nfd_attn_t* h, void* k8, void* v8t, int B, int H, int F, int T, int D, int kv_frames,
+                          int n_drop, void* stream) {
+    if (!h) return NFD_ERR_NULL;
+    if (!k8 || !v8t) return fail(h, NFD_ERR_NULL, "caches must be non-null");
+    if (B < 1 || H < 1 || F < 1 || T < 1 || D < 1 || kv_frames < 0 || n_drop < 0 || n_drop > kv_frames)
+        return fail(h, NFD_ERR_SHAPE, "invalid shape arguments");
+    if (kv_frames > F) return fail(h, NFD_ERR_CAPACITY, "kv_frames exceeds the cache capacity F");
+    if (D != nfd::mfma::kD) return fail(h, NFD_ERR_UNSUPPORTED, "the 8-bit cache is built for head width 64");
+    if ((int64_t)F * T > (int64_t)1 << 30 || (int64_t)B * H > (int64_t)1 << 24)
+        return fail(h, NFD_ERR_UNSUPPORTED, "shape beyond the 32-bit row indexing of the kernels");
+    if (n_drop == 0 || kv_frames == n_drop) return NFD_OK;
+    const int64_t Spad = ((int64_t)F * T + 63) / 64 * 64, BH = (int64_t)B * H;
+    hipStream_t st = (hipStream_t)stream;
+    // K codes: BH heads of Spad rows x 64 bytes, a frame = T rows; V codes: BH * 64 feature rows of Spad bytes,
+    // a frame = T bytes of each.  (One tensor at a time: the geometries differ.)
+    shift_frames(h, 1, k8, nullptr, BH, Spad * D, (int64_t)T * D, kv_frames, n_drop, st);
+    shift_frames(h, 1, v8t, nullptr, BH * D, Spad, (int64_t)T, kv_frames, n_drop, st);
+    return check_hip(h, hipGetLastError(), "8-bit kvcache shift launch");
 }
 
 // ---- speculative sampling bookkeeping (host only) ---------------------------------------------

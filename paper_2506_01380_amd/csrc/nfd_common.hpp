@@ -42,6 +42,10 @@ struct FwdParams {
     int n_splits;       // key splits per query tile
     int group_q_tiles;  // split launches: 1 = query tiles of one (head, split) get adjacent workgroup ids
     float scale_log2e;  // softmax scale * log2(e)
+    // 8-bit cache only (k: [BH, Spad, D] E4M3 codes, v: [BH, D, Spad] codes, value = code * scale[bh]):
+    const float* k_scale;  // [BH]
+    const float* v_scale;  // [BH]
+    int Spad;              // F * T rounded up to a multiple of 64: row count of k, row length of v
 };
 
 __device__ __forceinline__ int kmax_of_row(int row, int T, int P) { return (P + row / T + 1) * T; }
