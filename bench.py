@@ -257,11 +257,13 @@ def main():
 
     fp8kv = []
     if args.fp8kv:
-        for name in wl.CONFIGS:
-            c = wl.CONFIGS[name]
+        # the workload named on the command line if it is a cached form, otherwise every cached form
+        main_cached = cfg["q_frames"] < cfg["kv_frames"]
+        for name in ([args.workload] if main_cached else list(wl.CONFIGS)):
+            c = wl.CONFIGS[name] if name in wl.CONFIGS else wl.EXTRA_CONFIGS[name]
             if c["dtype"] != "bf16" or c["q_frames"] == c["kv_frames"]:
                 continue
-            r = time_workload(name, 200, 10, kv8=True)
+            r = time_workload(name, args.steps if main_cached else 200, args.warmup if main_cached else 10, kv8=True)
             r.pop("cfg")
             fp8kv.append({k: (round(v, 4) if isinstance(v, float) else v) for k, v in r.items()
                           if k in ("workload", "ms_per_step", "ms_median", "ms_min", "tflops", "frames_per_s")})

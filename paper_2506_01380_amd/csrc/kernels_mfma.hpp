@@ -301,12 +301,14 @@ attn_fwd_bf16_d64(FwdParams p) {
     // 8-bit cache, byte offsets.  K: lane (n, h) reads chunk 2*kp + h of key row 32*kb + n (the swizzle of a row
     // does not depend on kb): 16 features = two contraction steps.  V: lane (n, h) reads, of feature row
     // 32*dt + n, the keys 4h..4h+3 and 8+4h..8+4h+3 of the 16-key chunk 2*kb + g: the rows of P it multiplies.
+    // The cache stores them as 8 consecutive bytes at byte 8 * (h ^ s) of the chunk, s = bit 4 of the feature
+    // (the 32 lanes of one h would otherwise read half of the banks twice).
     const int f8 = chunk_swizzle8(n);
     int k_off8[2], v_off8[4];
 #pragma unroll
     for (int kp = 0; kp < 2; ++kp) k_off8[kp] = n * kD + 16 * ((2 * kp + h) ^ f8);
 #pragma unroll
-    for (int ch = 0; ch < 4; ++ch) v_off8[ch] = n * kBN + 16 * (ch ^ f8) + 4 * h;
+    for (int ch = 0; ch < 4; ++ch) v_off8[ch] = n * kBN + 16 * (ch ^ f8) + 8 * (h ^ ((n >> 4) & 1));
 
     if (t_begin < t_end) load_tile(t_begin, 0);
     if (t_begin + 1 < t_end) load_tile(t_begin + 1, 1);
@@ -370,8 +372,8 @@ attn_fwd_bf16_d64(FwdParams p) {
 #pragma unroll
                         for (int dt = 0; dt < 2; ++dt) {
                             if constexpr (KV8) {
-                                const uint32_t* vp8 = (const uint32_t*)(vs_ + 32 * dt * kBN + v_off8[2 * kb + g]);
-                                uint32_t w0 = vp8[0], w1 = vp8[2];
+                                const u32x2 w01 = *(const u32x2*)(vs_ + 32 * dt * kBN + v_off8[2 * kb + g]);
+                                uint32_t w0 = w01[0], w1 = w01[1];
                                 if (j0 + kBN > p.Sk) {  // last tile of the cache: codes past the end count as zero
                                     const int left = p.Sk - (j0 + 32 * kb + 16 * g + 4 * h);  // keys left from w0's first
                                     w0 = left >= 4 ? w0 : left <= 0 ? 0u : w0 & ((1u << (8 * left)) - 1u);

@@ -508,7 +508,24 @@ int nfd_kvcache_shift_fp8(nfd_attn_t* h, void* k8, void* v8t, int B, int H, int 
     // K codes: BH heads of Spad rows x 64 bytes, a frame = T rows; V codes: BH * 64 feature rows of Spad bytes,
     // a frame = T bytes of each.  (One tensor at a time: the geometries differ.)
     shift_frames(h, 1, k8, nullptr, BH, Spad * D, (int64_t)T * D, kv_frames, n_drop, st);
-    shift_frames(h, 1, v8t, nullptr, BH * D, Spad, (int64_t)T, kv_frames, n_drop, st);
+    if (T % 16 == 0) {  // whole 16-key groups move: the permuted order inside them is untouched
+        shift_frames(h, 1, v8t, nullptr, BH * D, Spad, (int64_t)T, kv_frames, n_drop, st);
+    } else {
+        // key by key through the workspace (plain order there), as many feature rows at a time as fit
+        const int64_t keep_keys = (int64_t)(kv_frames - n_drop) * T, rows = BH * D;
+        const int64_t fit = (int64_t)(h->workspace_bytes / (size_t)keep_keys);
+        if (fit < 1) return fail(h, NFD_ERR_ALLOC, "the workspace cannot stage one feature row of the 8-bit V cache");
+        unsigned char* v = (unsigned char*)v8t;
+        unsigned char* ws = (unsigned char*)h->workspace;
+        for (int64_t r0 = 0; r0 < rows; r0 += fit) {
+            const int64_t nr = std::min(fit, rows - r0);
+            const dim3 grid((unsigned)std::min<int64_t>((keep_keys + 255) / 256, 1024), (unsigned)std::min<int64_t>(nr, 65535));
+            hipLaunchKernelGGL(nfd::v8t_move_keys, grid, dim3(256), 0, st, ws, v + r0 * Spad, nr, keep_keys, Spad, (int64_t)0,
+                               (int64_t)n_drop * T, keep_keys, 0, 1, r0);
+            hipLaunchKernelGGL(nfd::v8t_move_keys, grid, dim3(256), 0, st, v + r0 * Spad, ws, nr, Spad, keep_keys, (int64_t)0,
+                               (int64_t)0, keep_keys, 1, 0, r0);
+        }
+    }
     return check_hip(h, hipGetLastError(), "8-bit kvcache shift launch");
 }
 

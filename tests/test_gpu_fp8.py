@@ -44,9 +44,36 @@ def _scales(B, H, seed, lo=0.01, hi=0.05):
     return (rng.uniform(lo, hi, size=(B, H)).astype(np.float32), rng.uniform(lo, hi, size=(B, H)).astype(np.float32))
 
 
+def _v_position(j, s):
+    """Byte position of key j inside a feature row of the library's V cache (s = bit 4 of the feature index): keys
+    are permuted inside aligned groups of 16 so that keys 4h..4h+3 and 8+4h..8+4h+3 sit in 8 consecutive bytes
+    at byte 8 * (h ^ s) of the group (see include/nfd_attn.h)."""
+    q = j & 15
+    return (j & ~15) | (8 * (((q >> 2) & 1) ^ s) + 4 * (q >> 3) + (q & 3))
+
+
+def _v_logical(hv):
+    """Device bytes [B, H, D, S] -> plain key order."""
+    S = hv.shape[3]
+    j = np.arange(S)
+    out = np.empty_like(hv)
+    for d in range(hv.shape[2]):
+        out[:, :, d, :] = hv[:, :, d, _v_position(j, (d >> 4) & 1)]
+    return out
+
+
+def _v_physical(lv):
+    S = lv.shape[3]
+    j = np.arange(S)
+    out = np.empty_like(lv)
+    for d in range(lv.shape[2]):
+        out[:, :, d, _v_position(j, (d >> 4) & 1)] = lv[:, :, d, :]
+    return out
+
+
 def _host_views(k8, v8, B, H, F, T, D=64):
     S = _spad(F, T)
-    return k8.cpu().numpy().reshape(B, H, S, D), v8.cpu().numpy().reshape(B, H, D, S)
+    return k8.cpu().numpy().reshape(B, H, S, D), _v_logical(v8.cpu().numpy().reshape(B, H, D, S))
 
 
 def _append(attn, k8, v8, ks, vs, kn, vn, B, H, F, T, pos):
@@ -153,7 +180,9 @@ def test_custom_scale_and_plan_shapes(attn):
 @pytest.mark.parametrize("B,H,T,F,kvf,drop,ws", [
     (1, 2, 16, 6, 6, 4, 0),      # keep <= drop: one disjoint copy; 16-byte vectors
     (2, 3, 48, 8, 7, 2, 0),      # overlapping: through the workspace
-    (1, 2, 5, 9, 9, 2, 0),       # n_drop * T not a multiple of 16: single bytes
+    (1, 2, 5, 9, 9, 2, 0),       # T not a multiple of 16: V moves key by key through the workspace
+    (1, 2, 5, 9, 9, 2, 4096),    # ... in two batches of feature rows (117 + 11)
+    (1, 3, 37, 6, 5, 1, 0),
     (1, 2, 48, 8, 8, 3, 4096),   # a workspace too small for staging: runs of n_drop frames
     (1, 1, 7, 5, 4, 4, 0),       # everything dropped: nothing moves
 ])
@@ -166,8 +195,8 @@ def test_shift_of_the_8bit_cache(B, H, T, F, kvf, drop, ws):
         S = _spad(F, T)
         rng = np.random.default_rng(T + F)
         hk = rng.integers(0, 256, size=(B, H, S, D), dtype=np.uint8)
-        hv = rng.integers(0, 256, size=(B, H, D, S), dtype=np.uint8)
-        k8, v8 = torch.from_numpy(hk.reshape(-1)).cuda(), torch.from_numpy(hv.reshape(-1)).cuda()
+        hv = rng.integers(0, 256, size=(B, H, D, S), dtype=np.uint8)  # in plain key order
+        k8, v8 = torch.from_numpy(hk.reshape(-1)).cuda(), torch.from_numpy(_v_physical(hv).reshape(-1)).cuda()
         nb.nfd_kvcache_shift_fp8(a.h, k8, v8, B, H, F, T, D, kvf, drop)
         torch.cuda.synchronize()
         gk, gv = _host_views(k8, v8, B, H, F, T)
