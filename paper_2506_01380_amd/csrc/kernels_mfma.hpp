@@ -83,6 +83,17 @@ struct __attribute__((aligned(16))) SmemRing8 {
 };
 __device__ __forceinline__ int chunk_swizzle8(int r) { return (r >> 2) & 3; }
 
+// 64-row workgroup shape over the 8-bit cache: the four wavefronts widen each tile ONCE, together, from the
+// ring of code tiles into a double-buffered pair of bf16 tiles in the bf16 kernel's layout (V with the 8 keys of
+// one matrix operand contiguous), one tile ahead of its use; the products then read bf16 fragments.  16
+// conversions per wavefront and tile instead of 64.
+struct __attribute__((aligned(16))) SmemRing8Wide {
+    unsigned char k[kRingSlots][kTileElems];
+    unsigned char v[kRingSlots][kTileElems];
+    __bf16 kb[2][kTileElems];
+    __bf16 vb[2][kTileElems];
+};
+
 // Eight E4M3 codes (two dwords, lowest byte first) widened to bf16; every E4M3 value is a bf16 value.
 __device__ __forceinline__ bf16x8 widen_e4m3x8(uint32_t w0, uint32_t w1) {
     const bf16x2 a = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w0, 1.0f, false);
@@ -194,7 +205,8 @@ attn_fwd_bf16_d64(FwdParams p) {
     constexpr int BM = kWaves * 32 * QT;
     constexpr int WR = 32 * QT;  // query rows per wavefront
     constexpr int PRIO = kMfmaPriority;
-    __shared__ typename std::conditional<KV8, SmemRing8, SmemRing>::type sm;
+    constexpr bool WIDE = KV8 && QT == 2;  // tiles widened once per workgroup (see SmemRing8Wide)
+    __shared__ typename std::conditional<WIDE, SmemRing8Wide, typename std::conditional<KV8, SmemRing8, SmemRing>::type>::type sm;
     const WorkItem wi = decode_work(p);
     if (!wi.valid) return;  // whole workgroup leaves together
 
@@ -226,7 +238,7 @@ attn_fwd_bf16_d64(FwdParams p) {
         for (int ks = 0; ks < 4; ++ks) {
             // contraction step ks, lane half h: features 16*ks + 8*h ..+7; with the 8-bit cache the features of
             // the 16-byte chunk 2*(ks/2) + h, first or second half (ks % 2) - the order the K reads deliver
-            const int d0 = KV8 ? 16 * (2 * (ks >> 1) + h) + 8 * (ks & 1) : 16 * ks + 8 * h;
+            const int d0 = KV8 && !WIDE ? 16 * (2 * (ks >> 1) + h) + 8 * (ks & 1) : 16 * ks + 8 * h;
             qf[qt][ks] = *(const bf16x8*)(qg + (int64_t)rc * kD + d0);
         }
     }
@@ -309,9 +321,44 @@ attn_fwd_bf16_d64(FwdParams p) {
     for (int kp = 0; kp < 2; ++kp) k_off8[kp] = n * kD + 16 * ((2 * kp + h) ^ f8);
 #pragma unroll
     for (int ch = 0; ch < 4; ++ch) v_off8[ch] = n * kBN + 16 * (ch ^ f8) + 8 * (h ^ ((n >> 4) & 1));
+    // Widened tiles (WIDE): V^T rows of 64 bf16 whose 16-byte chunk 2*ch + h holds the 8 keys lane half h needs of
+    // the 16-key chunk ch; read like K.  A lane widens the 16 codes of chunk cv_c of tile row cv_row of both
+    // tensors.  Eight consecutive lanes take the eight even (or odd) rows of the wavefront's 16: the 16-byte
+    // stores of such a group then fall on eight different chunk positions of the 128-byte rows (stores are
+    // served eight lanes at a time), and the 16-byte loads stay conflict-free (measured: 0 conflict cycles
+    // for both; 16 consecutive rows per 16 lanes cost a two-way conflict on either side).
+    int v_offw[4];
+#pragma unroll
+    for (int ch = 0; ch < 4; ++ch) v_offw[ch] = n * kD + 8 * ((2 * ch + h) ^ fk);
+    const int cv_row = 16 * wave + 2 * (lane & 7) + ((lane >> 3) & 1), cv_c = lane >> 4;
+    const int cv_src = cv_row * 64 + 16 * (cv_c ^ chunk_swizzle8(cv_row));
+    const int cv_f = chunk_swizzle(cv_row), cv_s = (cv_row >> 4) & 1;
+    const int cv_k0 = cv_row * kD + 8 * ((2 * cv_c) ^ cv_f), cv_k1 = cv_row * kD + 8 * ((2 * cv_c + 1) ^ cv_f);
+    const int cv_v0 = cv_row * kD + 8 * ((2 * cv_c + cv_s) ^ cv_f), cv_v1 = cv_row * kD + 8 * ((2 * cv_c + (cv_s ^ 1)) ^ cv_f);
+    auto widen_tile = [&](int t, int fslot, int buf) {
+        if constexpr (WIDE) {
+            const u32x4 rk = *(const u32x4*)(sm.k[fslot] + cv_src);
+            u32x4 rv = *(const u32x4*)(sm.v[fslot] + cv_src);
+            const int j0 = t * kBN;
+            if (j0 + kBN > p.Sk) {  // last tile of the cache: V codes at or past the end count as zero
+#pragma unroll
+                for (int x = 0; x < 2; ++x) {  // bytes 8x..8x+7: keys 4hh..4hh+3 and 8+4hh.. of the chunk, hh = x ^ s
+                    const int left = p.Sk - (j0 + 16 * cv_c + 4 * (x ^ cv_s));
+                    rv[2 * x] = left >= 4 ? rv[2 * x] : left <= 0 ? 0u : rv[2 * x] & ((1u << (8 * left)) - 1u);
+                    rv[2 * x + 1] = left >= 12 ? rv[2 * x + 1] : left <= 8 ? 0u : rv[2 * x + 1] & ((1u << (8 * (left - 8))) - 1u);
+                }
+            }
+            *(bf16x8*)(sm.kb[buf] + cv_k0) = widen_e4m3x8(rk[0], rk[1]);
+            *(bf16x8*)(sm.kb[buf] + cv_k1) = widen_e4m3x8(rk[2], rk[3]);
+            *(bf16x8*)(sm.vb[buf] + cv_v0) = widen_e4m3x8(rv[0], rv[1]);
+            *(bf16x8*)(sm.vb[buf] + cv_v1) = widen_e4m3x8(rv[2], rv[3]);
+        }
+    };
 
     if (t_begin < t_end) load_tile(t_begin, 0);
     if (t_begin + 1 < t_end) load_tile(t_begin + 1, 1);
+    if constexpr (WIDE)
+        if (t_begin + 2 < t_end) load_tile(t_begin + 2, 2);
     // The Q fragments are complete from here on and the compiler knows it: no later guard on them
     // can drain the tile prefetch.  (This also lands tiles 0 and 1, once per workgroup.)
     wait_vmem_all();
@@ -319,12 +366,12 @@ attn_fwd_bf16_d64(FwdParams p) {
     auto compute_tile = [&](int t, int slot) {
         const int j0 = t * kBN;
         if (wave_active && j0 < kmax_wave) {
-            const auto* ks_ = sm.k[slot];
-            const auto* vs_ = sm.v[slot];
+            const auto* ks_ = [&]() { if constexpr (WIDE) return sm.kb[slot]; else return sm.k[slot]; }();
+            const auto* vs_ = [&]() { if constexpr (WIDE) return sm.vb[slot]; else return sm.v[slot]; }();
             // ---- S^T = K . Q^T: all eight K fragments are requested before the first product ------
             f32x16 s_acc[2][QT];  // [kb][qt]
             bf16x8 kf[2][4];
-            if constexpr (KV8) {
+            if constexpr (KV8 && !WIDE) {
                 u32x4 raw[2][2];
 #pragma unroll
                 for (int kb = 0; kb < 2; ++kb)
@@ -371,7 +418,10 @@ attn_fwd_bf16_d64(FwdParams p) {
                     for (int g = 0; g < 2; ++g)
 #pragma unroll
                         for (int dt = 0; dt < 2; ++dt) {
-                            if constexpr (KV8) {
+                            if constexpr (WIDE) {
+                                vf[kb][g][dt] = lds_read_b128(vs_ + 32 * dt * kD + v_offw[2 * kb + g]);
+                                continue;
+                            } else if constexpr (KV8) {
                                 const u32x2 w01 = *(const u32x2*)(vs_ + 32 * dt * kBN + v_off8[2 * kb + g]);
                                 uint32_t w0 = w01[0], w1 = w01[1];
                                 if (j0 + kBN > p.Sk) {  // last tile of the cache: codes past the end count as zero
@@ -484,8 +534,29 @@ attn_fwd_bf16_d64(FwdParams p) {
         }
     };
 
+    if constexpr (WIDE) {
+        // Code tiles t+1 and t+2 are in the ring (t+3 on its way into the slot tile t left), tile t sits widened
+        // in buffer `buf`.  Per tile: one barrier; then every wavefront requests tile t+3, widens its share of
+        // tile t+1 into the other buffer and runs the products of tile t.  The barrier at the top of the next
+        // round makes the widened tile visible and frees both the buffer and the code slot just read.
+        __builtin_amdgcn_s_barrier();  // tile t_begin landed for all (the wait above covered this wavefront's loads)
+        if (t_begin < t_end) widen_tile(t_begin, 0, 0);
+        int fs = 1, buf = 0;  // ring slot of tile t+1, buffer of tile t
+        for (int t = t_begin; t < t_end; ++t) {
+            __builtin_amdgcn_sched_barrier(0);
+            if (t + 2 < t_end) asm volatile("s_waitcnt vmcnt(2) lgkmcnt(0)" ::: "memory");  // tile t+1 landed, own LDS traffic done
+            else asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+            __builtin_amdgcn_s_barrier();
+            __builtin_amdgcn_sched_barrier(0);
+            if (t + 3 < t_end) load_tile(t + 3, fs == 0 ? 2 : fs - 1);  // (fs + 2) % 3: the slot of tile t
+            if (t + 1 < t_end) widen_tile(t + 1, fs, buf ^ 1);
+            compute_tile(t, buf);
+            fs = fs == 2 ? 0 : fs + 1;
+            buf ^= 1;
+        }
+    }
     int slot = 0;
-    for (int t = t_begin; t < t_end; ++t) {
+    for (int t = t_begin; !WIDE && t < t_end; ++t) {
         // Tile t has landed for this wavefront once at most tile t+1's four loads are in flight;
         // after the barrier it has landed for all, and every wavefront is done with tile t-1, whose
         // slot the load of tile t+2 reuses.
