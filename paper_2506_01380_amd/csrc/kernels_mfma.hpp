@@ -322,19 +322,17 @@ attn_fwd_bf16_d64(FwdParams p) {
 #pragma unroll
     for (int ch = 0; ch < 4; ++ch) v_off8[ch] = n * kBN + 16 * (ch ^ f8) + 8 * (h ^ ((n >> 4) & 1));
     // Widened tiles (WIDE): V^T rows of 64 bf16 whose 16-byte chunk 2*ch + h holds the 8 keys lane half h needs of
-    // the 16-key chunk ch; read like K.  A lane widens the 16 codes of chunk cv_c of tile row cv_row of both
+    // the 16-key chunk ch; read like K, with K's offsets (k_off[ch]).  A lane widens the 16 codes of chunk cv_c of tile row cv_row of both
     // tensors.  Eight consecutive lanes take the eight even (or odd) rows of the wavefront's 16: the 16-byte
     // stores of such a group then fall on eight different chunk positions of the 128-byte rows (stores are
     // served eight lanes at a time), and the 16-byte loads stay conflict-free (measured: 0 conflict cycles
     // for both; 16 consecutive rows per 16 lanes cost a two-way conflict on either side).
-    int v_offw[4];
-#pragma unroll
-    for (int ch = 0; ch < 4; ++ch) v_offw[ch] = n * kD + 8 * ((2 * ch + h) ^ fk);
     const int cv_row = 16 * wave + 2 * (lane & 7) + ((lane >> 3) & 1), cv_c = lane >> 4;
     const int cv_src = cv_row * 64 + 16 * (cv_c ^ chunk_swizzle8(cv_row));
     const int cv_f = chunk_swizzle(cv_row), cv_s = (cv_row >> 4) & 1;
-    const int cv_k0 = cv_row * kD + 8 * ((2 * cv_c) ^ cv_f), cv_k1 = cv_row * kD + 8 * ((2 * cv_c + 1) ^ cv_f);
-    const int cv_v0 = cv_row * kD + 8 * ((2 * cv_c + cv_s) ^ cv_f), cv_v1 = cv_row * kD + 8 * ((2 * cv_c + (cv_s ^ 1)) ^ cv_f);
+    // destinations (elements): the two halves of a chunk go to chunk positions that differ in their lowest bit
+    const int cv_k0 = cv_row * kD + 8 * ((2 * cv_c) ^ cv_f);
+    const int cv_v0 = cv_row * kD + 8 * ((2 * cv_c + cv_s) ^ cv_f);
     auto widen_tile = [&](int t, int fslot, int buf) {
         if constexpr (WIDE) {
             const u32x4 rk = *(const u32x4*)(sm.k[fslot] + cv_src);
@@ -349,9 +347,9 @@ attn_fwd_bf16_d64(FwdParams p) {
                 }
             }
             *(bf16x8*)(sm.kb[buf] + cv_k0) = widen_e4m3x8(rk[0], rk[1]);
-            *(bf16x8*)(sm.kb[buf] + cv_k1) = widen_e4m3x8(rk[2], rk[3]);
+            *(bf16x8*)(sm.kb[buf] + (cv_k0 ^ 8)) = widen_e4m3x8(rk[2], rk[3]);
             *(bf16x8*)(sm.vb[buf] + cv_v0) = widen_e4m3x8(rv[0], rv[1]);
-            *(bf16x8*)(sm.vb[buf] + cv_v1) = widen_e4m3x8(rv[2], rv[3]);
+            *(bf16x8*)(sm.vb[buf] + (cv_v0 ^ 8)) = widen_e4m3x8(rv[2], rv[3]);
         }
     };
 
@@ -419,7 +417,7 @@ attn_fwd_bf16_d64(FwdParams p) {
 #pragma unroll
                         for (int dt = 0; dt < 2; ++dt) {
                             if constexpr (WIDE) {
-                                vf[kb][g][dt] = lds_read_b128(vs_ + 32 * dt * kD + v_offw[2 * kb + g]);
+                                vf[kb][g][dt] = lds_read_b128(vs_ + 32 * dt * kD + k_off[2 * kb + g]);
                                 continue;
                             } else if constexpr (KV8) {
                                 const u32x2 w01 = *(const u32x2*)(vs_ + 32 * dt * kBN + v_off8[2 * kb + g]);
