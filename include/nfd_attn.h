@@ -255,6 +255,9 @@ int nfd_attn_plan(nfd_dtype_t dtype, int B, int H, int F, int T, int D, int kv_f
  * Layouts (device memory, 16-byte aligned, owned by the caller):
  *   k8  : [B, H, Spad, D] codes          v8t : [B, H, D, Spad] codes (feature-major)
  *   Spad = F * T rounded up to a multiple of 64;  nfd_fp8_cache_bytes returns the size of EACH cache.
+ *   Inside every aligned group of 16 keys of a v8t row the order is permuted: key q = 4a + b of the group
+ *   (a = 0..3, b = 0..3) sits at byte 8 * ((a & 1) ^ s) + 4 * (a >> 1) + b, s = bit 4 of the feature index.
+ *   Both caches are written by nfd_kvcache_append_fp8 and moved by nfd_kvcache_shift_fp8 only.
  *   k_scale, v_scale : [B, H] fp32, positive.
  * Codes outside the first kv_frames * T keys are never used, whatever they are.  Supported: bf16 handle, D = 64.
  */
