@@ -238,3 +238,62 @@ def test_error_codes(attn):
         assert e.value.code == nb.NFD_ERR_UNSUPPORTED
     finally:
         a32.close()
+
+
+@pytest.mark.parametrize("T", [48, 20])  # 48: whole 16-key groups move; 20: V moves key by key
+def test_speculative_decode_loop_over_the_8bit_cache(T):
+    """The library's speculative bookkeeping driving the 8-bit cache: eviction (shift), quantising append of the
+    generated frames, attention, accept/reject with rollback.  A host mirror of the codes is kept with the
+    oracle's quantiser; codes are compared bit for bit and every step's attention with the fp64 oracle."""
+    from oracle import spec_driver as sd
+    B, H, D = 1, 3, 64
+    total, n_prompt, nframe, window, F = 18, 2, 3, 5, 8
+    rng = np.random.default_rng(500 + T)
+    actions = np.repeat(rng.integers(0, 3, size=(total, 1)), rng.integers(1, 5, size=total), axis=0)[:total].astype(np.int32)
+    mk = lambda: wl.round_to_bf16(rng.standard_normal((total, B, H, T, D)).astype(np.float32))
+    Q, K, V = mk(), mk(), mk()
+    frames = lambda X, idx: np.ascontiguousarray(np.concatenate([X[f] for f in idx], axis=2))
+    ks, vs = _scales(B, H, T, 0.01, 0.02)
+    a = nb.Attention("bf16")
+    try:
+        k8, v8 = _caches(B, H, F, T)
+        S = _spad(F, T)
+        hk = np.full((B, H, S, D), NAN_CODE, dtype=np.uint8)
+        hv = np.full((B, H, D, S), NAN_CODE, dtype=np.uint8)
+        prompt = list(range(n_prompt))
+        ksd, vsd = _append(a, k8, v8, ks, vs, frames(K, prompt), frames(V, prompt), B, H, F, T, 0)
+        f8.kvcache_append_fp8(hk, hv, frames(K, prompt), frames(V, prompt), T, 0, ks, vs)
+        s = nb.nfd_spec_init(F, window, nframe, n_prompt, total)
+        expect = sd.run(actions, n_prompt, nframe, window, F)
+        n_steps = 0
+        while True:
+            st = nb.nfd_spec_next(s)
+            if st is None:
+                break
+            ex = expect[n_steps]
+            n_steps += 1
+            if st.n_drop:
+                kv_before = st.frame_pos + st.n_drop
+                nb.nfd_kvcache_shift_fp8(a.h, k8, v8, B, H, F, T, D, kv_before, st.n_drop)
+                keep = (kv_before - st.n_drop) * T
+                hk[:, :, :keep] = hk[:, :, st.n_drop * T: kv_before * T].copy()
+                hv[:, :, :, :keep] = hv[:, :, :, st.n_drop * T: kv_before * T].copy()
+            gen = ex["generated"]
+            qn, kn, vn = frames(Q, gen), frames(K, gen), frames(V, gen)
+            nb.nfd_kvcache_append_fp8(a.h, k8, v8, ksd, vsd, _bf16(kn), _bf16(vn), B, H, F, T, D, st.frame_pos, st.n_frames)
+            f8.kvcache_append_fp8(hk, hv, kn, vn, T, st.frame_pos, ks, vs)
+            qd = _bf16(qn)
+            out = torch.empty_like(qd)
+            nb.nfd_block_causal_attn_fwd_fp8kv(a.h, qd, k8, v8, ksd, vsd, out, B, H, F, T, D, st.kv_frames, st.q_frames)
+            torch.cuda.synchronize()
+            n_valid = st.kv_frames * T
+            gk, gv = _host_views(k8, v8, B, H, F, T)
+            assert np.array_equal(gk[:, :, :n_valid], hk[:, :, :n_valid]), "step %d: K codes" % n_steps
+            assert np.array_equal(gv[:, :, :, :n_valid], hv[:, :, :, :n_valid]), "step %d: V codes" % n_steps
+            ref = f8.block_causal_attn_fp8kv(qn, hk, hv, ks, vs, T, st.kv_frames, st.q_frames)
+            d = out.float().cpu().numpy() - ref
+            assert np.abs(d).max() <= TOL_MAX_ABS and np.linalg.norm(d) / np.linalg.norm(ref) <= 5e-3, n_steps
+            assert nb.nfd_spec_accept(s, st, actions) == ex["kept"]
+        assert n_steps == len(expect) and s.done == total
+    finally:
+        a.close()
