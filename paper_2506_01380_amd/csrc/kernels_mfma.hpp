@@ -226,14 +226,23 @@ attn_fwd_bf16_d64(FwdParams p) {
     const __bf16* vg = (const __bf16*)p.v + (int64_t)wi.bh * p.Scap * kD;
 
     // ---- this wavefront's queries -------------------------------------------------------
-    const int rw0 = r0 + wave * WR;
+    // QT = 2: the wavefront owns the 32-row blocks `wave` and `wave + 4` of the workgroup's 256 rows, not two
+    // adjacent ones.  Where a frame boundary falls inside the workgroup, the later frame's extra key tiles are
+    // then shared by all four wavefronts (each running one block) instead of keeping the last wavefronts busy
+    // with two blocks while the first ones idle.  A ragged last query tile keeps adjacent blocks (2*wave,
+    // 2*wave + 1): there the rows past the end, not a frame boundary, decide which wavefronts have work.
+    const bool full_tile = r0 + BM <= p.Sq;
     int row[QT], kmax_lane[QT];
+    int kmin_blk[QT], kmax_blk[QT];  // key bound of a block's first / last row: mask needed above, nothing beyond
     bf16x8 qf[QT][4];
 #pragma unroll
     for (int qt = 0; qt < QT; ++qt) {
-        row[qt] = rw0 + 32 * qt + n;
+        const int b0 = r0 + 32 * (QT == 1 ? wave : full_tile ? wave + kWaves * qt : 2 * wave + qt);
+        row[qt] = b0 + n;
         const int rc = min(row[qt], p.Sq - 1);  // ragged tail: compute a duplicate, never store it
         kmax_lane[qt] = kmax_of_row(rc, p.T, p.P);
+        kmin_blk[qt] = kmax_of_row(min(b0, p.Sq - 1), p.T, p.P);
+        kmax_blk[qt] = kmax_of_row(min(b0 + 31, p.Sq - 1), p.T, p.P);
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
             // contraction step ks, lane half h: features 16*ks + 8*h ..+7; with the 8-bit cache the features of
@@ -242,10 +251,8 @@ attn_fwd_bf16_d64(FwdParams p) {
             qf[qt][ks] = *(const bf16x8*)(qg + (int64_t)rc * kD + d0);
         }
     }
-    const int rw_first = min(rw0, p.Sq - 1), rw_last = min(rw0 + WR - 1, p.Sq - 1);
-    const int kmin_wave = kmax_of_row(rw_first, p.T, p.P);  // tiles ending at or below need no mask
-    const int kmax_wave = kmax_of_row(rw_last, p.T, p.P);   // tiles starting at or above are skipped
-    const bool wave_active = rw0 < p.Sq;
+    const int kmax_wave = kmax_blk[QT - 1];  // tiles starting at or above are skipped (blocks ascend)
+    const bool wave_active = r0 + 32 * (QT == 1 || full_tile ? wave : 2 * wave) < p.Sq;
 
     f32x16 o_acc[2][QT];  // [dt][qt]: O^T rows 32*dt.., query block qt
 #pragma unroll
@@ -361,9 +368,11 @@ attn_fwd_bf16_d64(FwdParams p) {
     // can drain the tile prefetch.  (This also lands tiles 0 and 1, once per workgroup.)
     wait_vmem_all();
 
-    auto compute_tile = [&](int t, int slot) {
+    // QA = first block of the wavefront that still has visible keys in this tile (1: its earlier block is done)
+    auto tile_body = [&](int t, int slot, auto qa_tag) {
+        constexpr int QA = decltype(qa_tag)::value;
         const int j0 = t * kBN;
-        if (wave_active && j0 < kmax_wave) {
+        {
             const auto* ks_ = [&]() { if constexpr (WIDE) return sm.kb[slot]; else return sm.k[slot]; }();
             const auto* vs_ = [&]() { if constexpr (WIDE) return sm.vb[slot]; else return sm.v[slot]; }();
             // ---- S^T = K . Q^T: all eight K fragments are requested before the first product ------
@@ -397,13 +406,13 @@ attn_fwd_bf16_d64(FwdParams p) {
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb) {
 #pragma unroll
-                for (int qt = 0; qt < QT; ++qt)
+                for (int qt = QA; qt < QT; ++qt)
 #pragma unroll
                     for (int r = 0; r < 16; ++r) s_acc[kb][qt][r] = 0.f;
 #pragma unroll
                 for (int ks = 0; ks < 4; ++ks)
 #pragma unroll
-                    for (int qt = 0; qt < QT; ++qt)
+                    for (int qt = QA; qt < QT; ++qt)
                         s_acc[kb][qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kb][ks], qf[qt][ks], s_acc[kb][qt], 0, 0, 0);
             }
             __builtin_amdgcn_sched_barrier(0);
@@ -439,11 +448,11 @@ attn_fwd_bf16_d64(FwdParams p) {
                         }
             };
             // ---- mask (only tiles that cross some row's bound) ---------------------------------
-            if (j0 + kBN > kmin_wave) {
+            if (j0 + kBN > kmin_blk[QA]) {
 #pragma unroll
                 for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-                    for (int qt = 0; qt < QT; ++qt)
+                    for (int qt = QA; qt < QT; ++qt)
 #pragma unroll
                         for (int r = 0; r < 16; ++r) {
                             const int key = j0 + 32 * kb + 8 * (r >> 2) + 4 * h + (r & 3);
@@ -456,7 +465,7 @@ attn_fwd_bf16_d64(FwdParams p) {
             auto form_p = [&]() {  // P = exp2(c*s - c*m_used) in bf16; row sums by plain fp32 adds (the
                                    // packed dot instruction shares the matrix pipe and would stall MFMAs)
 #pragma unroll
-                for (int qt = 0; qt < QT; ++qt) {
+                for (int qt = QA; qt < QT; ++qt) {
                     const float mc = m_used[qt] * c;
                     float l = 0.f, l2 = 0.f;
 #pragma unroll
@@ -487,10 +496,10 @@ attn_fwd_bf16_d64(FwdParams p) {
 #pragma unroll
                     for (int b = 0; b < 2; ++b)
 #pragma unroll
-                        for (int e = 0; e < QT; ++e) asm volatile("" : "+v"(pf[a][b][e]));
+                        for (int e = QA; e < QT; ++e) asm volatile("" : "+v"(pf[a][b][e]));
                 bad = false;
 #pragma unroll
-                for (int qt = 0; qt < QT; ++qt) bad |= !(l_tile[qt] < kOptimisticLimit);
+                for (int qt = QA; qt < QT; ++qt) bad |= !(l_tile[qt] < kOptimisticLimit);
             }
             // V^T fragments are requested once P is formed (earlier they would not fit the register
             // file next to the scores kept for the rare exact pass); the latency passes behind the
@@ -498,7 +507,7 @@ attn_fwd_bf16_d64(FwdParams p) {
             read_v_frags();
             if (__builtin_amdgcn_ballot_w64(bad) != 0) {  // exact path: this tile's max, rescale, redo
 #pragma unroll
-                for (int qt = 0; qt < QT; ++qt) {
+                for (int qt = QA; qt < QT; ++qt) {
                     float a = fmaxf(s_acc[0][qt][0], s_acc[1][qt][0]);
 #pragma unroll
                     for (int r = 1; r < 16; ++r) a = fmaxf(fmaxf(a, s_acc[0][qt][r]), s_acc[1][qt][r]);
@@ -515,7 +524,7 @@ attn_fwd_bf16_d64(FwdParams p) {
                 form_p();
             }
 #pragma unroll
-            for (int qt = 0; qt < QT; ++qt) l_sum[qt] += l_tile[qt];
+            for (int qt = QA; qt < QT; ++qt) l_sum[qt] += l_tile[qt];
             // ---- O^T += V^T . P^T -----------------------------------------------------------------
             __builtin_amdgcn_sched_barrier(0);
             __builtin_amdgcn_s_setprio(PRIO);
@@ -526,51 +535,75 @@ attn_fwd_bf16_d64(FwdParams p) {
 #pragma unroll
                     for (int dt = 0; dt < 2; ++dt)
 #pragma unroll
-                        for (int qt = 0; qt < QT; ++qt)
+                        for (int qt = QA; qt < QT; ++qt)
                             o_acc[dt][qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[kb][g][dt], pf[kb][g][qt], o_acc[dt][qt], 0, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
         }
     };
-
+    // The tile loop runs twice in sequence for QT = 2: tiles in which both blocks of the wavefront have visible
+    // keys, then the tiles only its later block still sees (two loops rather than a branch inside one: each keeps
+    // its own, smaller, set of live registers).  Every wavefront passes the same number of barriers.
+    int slot = 0;         // ring slot of tile t (of tile t+1 with widened tiles)
+    int buf = 0;          // widened tiles: buffer of tile t
+    auto run_tiles = [&](int t_from, int t_to, auto qa_tag) {
+        constexpr int QA = decltype(qa_tag)::value;
+        for (int t = t_from; t < t_to; ++t) {
+            __builtin_amdgcn_sched_barrier(0);
+            if constexpr (WIDE) {
+                // Code tiles t+1 and t+2 are in the ring (t+3 on its way into the slot tile t left), tile t sits
+                // widened in buffer `buf`.  Per tile: one barrier; then every wavefront requests tile t+3, widens
+                // its share of tile t+1 into the other buffer and runs the products of tile t.  The barrier at the
+                // top of the next round makes the widened tile visible and frees the buffer and the code slot read.
+                if (t + 2 < t_end) asm volatile("s_waitcnt vmcnt(2) lgkmcnt(0)" ::: "memory");  // tile t+1 landed, own LDS traffic done
+                else asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+                __builtin_amdgcn_s_barrier();
+                __builtin_amdgcn_sched_barrier(0);
+                if (t + 3 < t_end) load_tile(t + 3, slot == 0 ? 2 : slot - 1);  // (slot + 2) % 3: the slot of tile t
+                if (t + 1 < t_end) widen_tile(t + 1, slot, buf ^ 1);
+                if (QA == 0 || (wave_active && t * kBN < kmax_wave)) tile_body(t, buf, qa_tag);
+                buf ^= 1;
+            } else {
+                // Tile t has landed for this wavefront once at most tile t+1's loads are in flight (four; two with
+                // the 8-bit cache); after the barrier it has landed for all, and every wavefront is done with tile
+                // t-1, whose slot the load of tile t+2 reuses.
+                if (t + 1 < t_end) {
+                    if constexpr (KV8) asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
+                    else asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+                } else {
+                    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                }
+                __builtin_amdgcn_s_barrier();
+                __builtin_amdgcn_sched_barrier(0);
+                if (t + 2 < t_end) load_tile(t + 2, slot == 0 ? 2 : slot - 1);  // (slot + 2) % 3
+                if (QA == 0 || (wave_active && t * kBN < kmax_wave)) tile_body(t, slot, qa_tag);
+            }
+            slot = slot == 2 ? 0 : slot + 1;
+        }
+    };
     if constexpr (WIDE) {
-        // Code tiles t+1 and t+2 are in the ring (t+3 on its way into the slot tile t left), tile t sits widened
-        // in buffer `buf`.  Per tile: one barrier; then every wavefront requests tile t+3, widens its share of
-        // tile t+1 into the other buffer and runs the products of tile t.  The barrier at the top of the next
-        // round makes the widened tile visible and frees both the buffer and the code slot just read.
         __builtin_amdgcn_s_barrier();  // tile t_begin landed for all (the wait above covered this wavefront's loads)
         if (t_begin < t_end) widen_tile(t_begin, 0, 0);
-        int fs = 1, buf = 0;  // ring slot of tile t+1, buffer of tile t
-        for (int t = t_begin; t < t_end; ++t) {
-            __builtin_amdgcn_sched_barrier(0);
-            if (t + 2 < t_end) asm volatile("s_waitcnt vmcnt(2) lgkmcnt(0)" ::: "memory");  // tile t+1 landed, own LDS traffic done
-            else asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
-            __builtin_amdgcn_s_barrier();
-            __builtin_amdgcn_sched_barrier(0);
-            if (t + 3 < t_end) load_tile(t + 3, fs == 0 ? 2 : fs - 1);  // (fs + 2) % 3: the slot of tile t
-            if (t + 1 < t_end) widen_tile(t + 1, fs, buf ^ 1);
-            compute_tile(t, buf);
-            fs = fs == 2 ? 0 : fs + 1;
-            buf ^= 1;
-        }
+        slot = 1;
     }
-    int slot = 0;
-    for (int t = t_begin; !WIDE && t < t_end; ++t) {
-        // Tile t has landed for this wavefront once at most tile t+1's four loads are in flight;
-        // after the barrier it has landed for all, and every wavefront is done with tile t-1, whose
-        // slot the load of tile t+2 reuses.
-        __builtin_amdgcn_sched_barrier(0);
-        if (t + 1 < t_end) {  // all but the next tile's loads of this wavefront (four; two with the 8-bit cache)
-            if constexpr (KV8) asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
-            else asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
-        } else {
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    if constexpr (QT == 2) {
+        // tiles below the earlier block's bound (none for a wavefront past the end of a ragged last query tile)
+        const int t_mid = wave_active ? max(t_begin, min(t_end, (kmax_blk[0] + kBN - 1) / kBN)) : t_begin;
+        run_tiles(t_begin, t_mid, std::integral_constant<int, 0>{});
+        run_tiles(t_mid, t_end, std::integral_constant<int, 1>{});
+    } else {
+        const int t_mid = wave_active ? max(t_begin, min(t_end, (kmax_wave + kBN - 1) / kBN)) : t_begin;
+        run_tiles(t_begin, t_mid, std::integral_constant<int, 0>{});
+        for (int t = t_mid; t < t_end; ++t) {  // tiles this wavefront sees nothing of: keep the ring turning
+            if (t + 1 < t_end) {
+                if constexpr (KV8) asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
+                else asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+            } else {
+                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            }
+            __builtin_amdgcn_s_barrier();
+            if (t + 2 < t_end) load_tile(t + 2, slot == 0 ? 2 : slot - 1);
+            slot = slot == 2 ? 0 : slot + 1;
         }
-        __builtin_amdgcn_s_barrier();
-        __builtin_amdgcn_sched_barrier(0);
-        const int slot2 = slot == 0 ? 2 : slot - 1;  // (slot + 2) % 3
-        if (t + 2 < t_end) load_tile(t + 2, slot2);
-        compute_tile(t, slot);
-        slot = slot == 2 ? 0 : slot + 1;
     }
 
     if (!wave_active) return;
