@@ -74,3 +74,66 @@ def test_forward_and_backward_on_random_shapes(attn, B, H, T, kvf, qf, F):
     close(_host(dv)[:, :, :Sk], rdv[:, :, :Sk], "dv")
     assert np.abs(lse.cpu().numpy() - rlse).max() <= 2e-4
     assert np.all(_host(dk)[:, :, Sk:] == 0) and np.all(_host(dv)[:, :, Sk:] == 0)
+
+
+def _shapes_many_heads(n, seed):
+    """Enough (batch, head) units that the plan takes the 64-row wavefront shape (two interleaved row blocks per
+    wavefront, two tile loops; with the 8-bit cache the tiles widened once per workgroup)."""
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < n:
+        T = int(rng.choice([1, 3, 17, 40, 64, 100, 130, 200, 336]))
+        kvf = int(rng.integers(1, 12))
+        if kvf * T > 1400 or kvf * T < 200:
+            continue
+        qf = int(rng.integers(1, kvf + 1))
+        out.append((int(rng.choice([4, 8, 9])), int(rng.choice([8, 16, 9])), T, kvf, qf, kvf + int(rng.integers(0, 2))))
+    return out
+
+
+_FIXED_MANY_HEADS = [
+    (8, 8, 1, 300, 300, 300),    # T = 1: a frame boundary after every row
+    (8, 8, 3, 150, 100, 150),    # cached form, tiny frames
+    (4, 16, 17, 40, 40, 41),     # many boundaries inside one workgroup, ragged last tile
+    (4, 16, 336, 4, 4, 4),       # the paper's frame size: one boundary in three of four workgroups
+    (8, 8, 256, 3, 3, 3),        # frames = workgroups: no boundary inside any
+]
+
+
+@pytest.mark.parametrize("B,H,T,kvf,qf,F", _shapes_many_heads(14, 20260614) + _FIXED_MANY_HEADS)
+def test_forward_many_heads_both_caches(attn, B, H, T, kvf, qf, F):
+    from oracle import fp8_cache as f8
+    D = 64
+    plan = nb.nfd_attn_plan(nb.NFD_BF16, B, H, F, T, D, kvf, qf)
+    assert plan["block_m"] == 256, plan
+    seed = wl.BASE_SEED + 2000 + 7 * T + 31 * kvf + qf
+    q, k, v = wl.make_qkv(B, H, D, T, kvf, qf, F, "bf16", seed=seed)
+    if F > kvf:
+        k[:, :, kvf * T:] = np.nan
+        v[:, :, kvf * T:] = np.nan
+    qd = _dev(q)
+    out = attn.forward(qd, _dev(k), _dev(v), T, kv_frames=kvf, q_frames=qf)
+    # the same keys and values through the 8-bit cache
+    Sk = kvf * T
+    n8 = nb.nfd_fp8_cache_bytes(B, H, F, T, D)
+    k8 = torch.full((n8,), 0x7F, dtype=torch.uint8, device="cuda")
+    v8 = torch.full((n8,), 0x7F, dtype=torch.uint8, device="cuda")
+    rng = np.random.default_rng(seed)
+    ks, vs = (rng.uniform(0.01, 0.03, size=(B, H)).astype(np.float32) for _ in range(2))
+    ksd, vsd = torch.from_numpy(ks).cuda(), torch.from_numpy(vs).cuda()
+    nb.nfd_kvcache_append_fp8(attn.h, k8, v8, ksd, vsd, _dev(k[:, :, :Sk]), _dev(v[:, :, :Sk]), B, H, F, T, D, 0, kvf)
+    out8 = torch.empty_like(qd)
+    nb.nfd_block_causal_attn_fwd_fp8kv(attn.h, qd, k8, v8, ksd, vsd, out8, B, H, F, T, D, kvf, qf)
+    torch.cuda.synchronize()
+
+    def close(got, want, tag):
+        assert np.all(np.isfinite(got)), tag
+        d = got - want
+        rel = np.linalg.norm(d) / np.linalg.norm(want)
+        assert rel <= 5e-3 and np.abs(d).max() <= 2e-2, (tag, rel, np.abs(d).max())
+
+    kz, vz = np.nan_to_num(k), np.nan_to_num(v)
+    close(_host(out), orc.block_causal_attn(q, kz, vz, T, kv_frames=kvf, q_frames=qf), "bf16 cache")
+    kq = f8.e4m3_decode(f8.quantize(kz[:, :, :Sk], ks[:, :, None, None])) * ks[:, :, None, None].astype(np.float64)
+    vq = f8.e4m3_decode(f8.quantize(vz[:, :, :Sk], vs[:, :, None, None])) * vs[:, :, None, None].astype(np.float64)
+    close(_host(out8), orc.block_causal_attn(q, kq, vq, T, kv_frames=kvf, q_frames=qf), "8-bit cache")
