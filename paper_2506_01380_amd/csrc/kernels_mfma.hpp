@@ -1,8 +1,8 @@
 // bf16 matrix-core forward kernel for head width 64 (gfx950 / CDNA4).
 //
 // Flash-style online softmax.  A workgroup of 4 wavefronts owns 256 consecutive query rows of
-// one (batch, head); each wavefront owns 64 of them as two 32-wide column blocks of the
-// TRANSPOSED score matrix:
+// one (batch, head); each wavefront owns 64 of them as two 32-wide column blocks (blocks w and
+// w + 4 of the workgroup's eight) of the TRANSPOSED score matrix:
 //
 //   S^T[key, query] = K_tile[key, :] . Q^T[:, query]       v_mfma_f32_32x32x16_bf16, A = K (LDS), B = Q^T (registers)
 //   O^T[d,   query] += V_tile^T[d, key] . P^T[key, query]  A = V^T (LDS, transposing read), B = P^T (registers)
@@ -76,7 +76,8 @@ struct __attribute__((aligned(16))) SmemRing {
 // 8-bit cache (E4M3 codes): a K tile is 64 keys x 64 features, a V tile 64 features x 64 keys (V is stored
 // feature-major), both 64 rows of 64 bytes.  One wave instruction of 16-byte loads fills 16 tile rows, so a tile
 // is one load per wavefront and tensor.  The 16-byte chunk c of row r sits at chunk position c ^ ((r >> 2) & 3):
-// the 16-byte fragment reads of 16 consecutive rows (one chunk each) then cover all 64 banks exactly once.
+// measured conflict-free for the 16-byte fragment reads (lane n of a half-wavefront reads one chunk of row n;
+// such loads are served in groups of lanes {0-3, 12-15, 20-23, 24-27}, {4-7, 8-11, 16-19, 28-31}, same + 32).
 struct __attribute__((aligned(16))) SmemRing8 {
     unsigned char k[kRingSlots][kTileElems];
     unsigned char v[kRingSlots][kTileElems];
@@ -195,15 +196,15 @@ __device__ __forceinline__ void store_rows(const FwdParams& p, const WorkItem& w
 // matrix work per tile and wavefront, i.e. a shorter chain per key tile, for calls with few query rows whose
 // time is the length of that chain (cached forms); it reads twice the LDS bytes per FLOP.
 //
-// KV8: K and V come from the 8-bit cache (see SmemRing8) and are widened to bf16 on their way from LDS into
-// the matrix operands; the per-head scales are folded into the softmax scale (K) and the final write (V), so
-// the arithmetic between the operands is the same as for a bf16 cache.  The feature order inside the first
-// product's contraction is permuted (a 16-byte read serves two steps), the same way for K and Q.
+// KV8: K and V come from the 8-bit cache and are widened to bf16 (exact) before they reach the matrix operands;
+// the per-head scales are folded into the softmax scale (K) and the final write (V), so the arithmetic between
+// the operands is the same as for a bf16 cache.  QT = 1: every wavefront widens its own fragments on their way
+// out of LDS (SmemRing8); the feature order inside the first product's contraction is then permuted (a 16-byte
+// read serves two steps), the same way for K and Q.  QT = 2: the workgroup widens each tile once (SmemRing8Wide).
 template <int QT, bool KV8 = false>
 __global__ void __launch_bounds__(kWaves * 64, QT == 2 ? 2 : 3)
 attn_fwd_bf16_d64(FwdParams p) {
     constexpr int BM = kWaves * 32 * QT;
-    constexpr int WR = 32 * QT;  // query rows per wavefront
     constexpr int PRIO = kMfmaPriority;
     constexpr bool WIDE = KV8 && QT == 2;  // tiles widened once per workgroup (see SmemRing8Wide)
     __shared__ typename std::conditional<WIDE, SmemRing8Wide, typename std::conditional<KV8, SmemRing8, SmemRing>::type>::type sm;
