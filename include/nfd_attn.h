@@ -271,8 +271,9 @@ int nfd_kvcache_append_fp8(nfd_attn_t* h, void* k8, void* v8t, const float* k_sc
                            int n_frames, void* stream);
 
 /* nfd_kvcache_shift for the 8-bit caches: frames n_drop .. kv_frames-1 move to frames 0 .. ; same strategies
- * and errors (NFD_ERR_UNSUPPORTED for D != 64).  Vector copies when n_drop * T is a multiple of 16, single
- * bytes otherwise. */
+ * and errors (NFD_ERR_UNSUPPORTED for D != 64).  When T is a multiple of 16 whole key groups move (16-byte
+ * vectors); otherwise V moves key by key through the handle's workspace, which must hold at least one feature
+ * row of the kept keys ((kv_frames - n_drop) * T bytes), else NFD_ERR_ALLOC before anything is launched. */
 int nfd_kvcache_shift_fp8(nfd_attn_t* h, void* k8, void* v8t, int B, int H, int F, int T, int D, int kv_frames,
                           int n_drop, void* stream);
 

@@ -504,6 +504,9 @@ int nfd_kvcache_shift_fp8(nfd_attn_t* h, void* k8, void* v8t, int B, int H, int 
         return fail(h, NFD_ERR_UNSUPPORTED, "shape beyond the 32-bit row indexing of the kernels");
     if (n_drop == 0 || kv_frames == n_drop) return NFD_OK;
     const int64_t Spad = ((int64_t)F * T + 63) / 64 * 64, BH = (int64_t)B * H;
+    const int64_t keep_keys = (int64_t)(kv_frames - n_drop) * T;
+    if (T % 16 != 0 && h->workspace_bytes < (size_t)keep_keys)  // checked before anything is launched
+        return fail(h, NFD_ERR_ALLOC, "the workspace cannot stage one feature row of the 8-bit V cache");
     hipStream_t st = (hipStream_t)stream;
     // K codes: BH heads of Spad rows x 64 bytes, a frame = T rows; V codes: BH * 64 feature rows of Spad bytes,
     // a frame = T bytes of each.  (One tensor at a time: the geometries differ.)
@@ -512,9 +515,8 @@ int nfd_kvcache_shift_fp8(nfd_attn_t* h, void* k8, void* v8t, int B, int H, int 
         shift_frames(h, 1, v8t, nullptr, BH * D, Spad, (int64_t)T, kv_frames, n_drop, st);
     } else {
         // key by key through the workspace (plain order there), as many feature rows at a time as fit
-        const int64_t keep_keys = (int64_t)(kv_frames - n_drop) * T, rows = BH * D;
-        const int64_t fit = (int64_t)(h->workspace_bytes / (size_t)keep_keys);
-        if (fit < 1) return fail(h, NFD_ERR_ALLOC, "the workspace cannot stage one feature row of the 8-bit V cache");
+        const int64_t rows = BH * D;
+        const int64_t fit = (int64_t)(h->workspace_bytes / (size_t)keep_keys);  // >= 1, checked above
         unsigned char* v = (unsigned char*)v8t;
         unsigned char* ws = (unsigned char*)h->workspace;
         for (int64_t r0 = 0; r0 < rows; r0 += fit) {

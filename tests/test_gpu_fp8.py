@@ -238,6 +238,19 @@ def test_error_codes(attn):
         assert e.value.code == nb.NFD_ERR_UNSUPPORTED
     finally:
         a32.close()
+    # key-wise V move (T not a multiple of 16) with a workspace that cannot hold one feature row
+    tiny = nb.Attention("bf16", workspace_bytes=16)
+    try:
+        k8b, v8b = _caches(1, 1, 4, 7)
+        with pytest.raises(nb.NfdError) as e:
+            nb.nfd_kvcache_shift_fp8(tiny.h, k8b, v8b, 1, 1, 4, 7, D, 4, 1)
+        assert e.value.code == nb.NFD_ERR_ALLOC
+        with pytest.raises(nb.NfdError) as e:
+            nb.nfd_kvcache_shift_fp8(tiny.h, k8b, v8b, 1, 1, 4, 7, D, 5, 1)
+        assert e.value.code == nb.NFD_ERR_CAPACITY
+        nb.nfd_kvcache_shift_fp8(tiny.h, k8b, v8b, 1, 1, 4, 7, D, 3, 0)  # nothing to drop: no launch, no error
+    finally:
+        tiny.close()
 
 
 @pytest.mark.parametrize("T", [48, 20])  # 48: whole 16-key groups move; 20: V moves key by key
