@@ -131,3 +131,14 @@ def test_every_work_item_is_dealt_exactly_once(BH, nq, ns, group):
         order = [nb.nfd_attn_work_item(BH, nq, ns, 0, b)[1] for b in range(n)]
         first_of = {q: order.index(q) for q in range(nq)}
         assert all(first_of[q + 1] <= first_of[q] for q in range(nq - 1))
+
+
+def test_fp8_cache_bytes_rounds_the_key_count_to_whole_tiles():
+    assert nb.nfd_fp8_cache_bytes(1, 16, 40, 336, 64) == 16 * 13440 * 64          # 40 * 336 = 210 tiles exactly
+    assert nb.nfd_fp8_cache_bytes(2, 3, 5, 7, 64) == 2 * 3 * 64 * 64              # 35 keys -> one tile
+    assert nb.nfd_fp8_cache_bytes(1, 1, 1, 65, 64) == 128 * 64
+    import ctypes
+    n = ctypes.c_size_t(0)
+    assert nb.lib().nfd_fp8_cache_bytes(1, 1, 1, 16, 128, ctypes.byref(n)) == nb.NFD_ERR_UNSUPPORTED
+    assert nb.lib().nfd_fp8_cache_bytes(0, 1, 1, 16, 64, ctypes.byref(n)) == nb.NFD_ERR_SHAPE
+    assert nb.lib().nfd_fp8_cache_bytes(1, 1, 1, 16, 64, None) == nb.NFD_ERR_NULL
