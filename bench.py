@@ -135,9 +135,9 @@ def main():
         torch.cuda.synchronize()
         del kc, vc, kn, vn
 
-    def time_rope(name, steps, warmup):
+    def time_rope(name, steps, warmup, kv8=False):
         """The step before the attention call: rotate q and k of the workload's query frames, write k and v
-        into the cache.  HBM-bound streaming: 3 tensors in, 3 out."""
+        into the cache.  HBM-bound streaming: 3 tensors in, 3 out (kv8: k and v out as 8-bit codes)."""
         c = wl.CONFIGS[name]
         B, H, D, T, kvf, qf, F = (c[x] for x in ("B", "H", "D", "T", "kv_frames", "q_frames", "F"))
         grid = (24, T // 24)          # 24 x 14 latent grid at T = 336, 24 x 24 at T = 576
@@ -145,14 +145,22 @@ def main():
         gen = torch.Generator(device="cuda").manual_seed(c["seed"] + 5)
         mk = lambda *s: torch.randn(*s, device="cuda", generator=gen, dtype=torch.float32).to(torch.bfloat16)
         sets = []
+        if kv8:
+            n8 = nb.nfd_fp8_cache_bytes(B, H, F, T, D)
+            ksc = torch.full((B, H), 6.0 / 448.0, device="cuda")
+            vsc = torch.full((B, H), 6.0 / 448.0, device="cuda")
         for _ in range(4):
+            cache = (lambda: torch.zeros(n8, dtype=torch.uint8, device="cuda")) if kv8 else \
+                (lambda: torch.zeros(B, H, F * T, D, device="cuda", dtype=torch.bfloat16))
             sets.append((mk(B, H, qf * T, D), mk(B, H, qf * T, D), mk(B, H, qf * T, D),
-                         torch.empty(B, H, qf * T, D, device="cuda", dtype=torch.bfloat16),
-                         torch.zeros(B, H, F * T, D, device="cuda", dtype=torch.bfloat16),
-                         torch.zeros(B, H, F * T, D, device="cuda", dtype=torch.bfloat16)))
+                         torch.empty(B, H, qf * T, D, device="cuda", dtype=torch.bfloat16), cache(), cache()))
 
         def step(i):
             q, kn, vn, qo, kc, vc = sets[i % len(sets)]
+            if kv8:
+                nb.nfd_rope_kvcache_append_fp8(attn.h, q, qo, kc, vc, ksc, vsc, kn, vn, B, H, F, T, D, kvf - qf, qf, 0,
+                                               grid[0], grid[1], sections[0], sections[1], sections[2], 10000.0)
+                return
             nb.nfd_rope_kvcache_append(attn.h, q, qo, kc, vc, kn, vn, B, H, F, T, D, kvf - qf, qf, 0,
                                        grid[0], grid[1], sections[0], sections[1], sections[2], 10000.0)
 
@@ -166,8 +174,8 @@ def main():
         e1.record()
         torch.cuda.synchronize()
         ms = e0.elapsed_time(e1) / steps
-        nbytes = 6 * B * H * qf * T * D * 2  # q, k, v read; q, k, v written
-        return dict(kernel="rope_kvcache_append", workload=name, us_per_call=round(ms * 1e3, 2), bytes=nbytes,
+        nbytes = (5 if kv8 else 6) * B * H * qf * T * D * 2  # q, k, v read; q, k, v written (k, v as one byte each with kv8)
+        return dict(kernel="rope_kvcache_append" + ("<.., true> (8-bit cache)" if kv8 else ""), workload=name, us_per_call=round(ms * 1e3, 2), bytes=nbytes,
                     gbs=round(nbytes / ms * 1e-6, 1), frac_hbm_peak=round(nbytes / ms * 1e-6 / PEAK_HBM_GBS, 4))
 
     def time_bwd(name, steps, warmup):
@@ -243,6 +251,9 @@ def main():
     if args.rope:
         pre_op = time_rope(args.workload, args.steps, args.warmup)
         print(json.dumps(pre_op), file=sys.stderr, flush=True)
+        if args.fp8kv:
+            pre_op = [pre_op, time_rope(args.workload, args.steps, args.warmup, kv8=True)]
+            print(json.dumps(pre_op[1]), file=sys.stderr, flush=True)
 
     others = []
     if args.all:

@@ -270,6 +270,16 @@ int nfd_kvcache_append_fp8(nfd_attn_t* h, void* k8, void* v8t, const float* k_sc
                            const void* k_new, const void* v_new, int B, int H, int F, int T, int D, int frame_pos,
                            int n_frames, void* stream);
 
+/* nfd_rope_kvcache_append writing the 8-bit caches: q is rotated into q_out; the rotated key, rounded to bf16
+ * exactly as for a bf16 cache, and the value are quantised as by nfd_kvcache_append_fp8.  The codes equal those of
+ * nfd_rope_kvcache_append into a bf16 buffer followed by nfd_kvcache_append_fp8.  Errors as for
+ * nfd_rope_kvcache_append, plus NFD_ERR_NULL for the scales and NFD_ERR_UNSUPPORTED for fp32 handles, D != 64 or
+ * tensors that are not 16-byte aligned. */
+int nfd_rope_kvcache_append_fp8(nfd_attn_t* h, const void* q, void* q_out, void* k8, void* v8t, const float* k_scale,
+                                const float* v_scale, const void* k_new, const void* v_new, int B, int H, int F,
+                                int T, int D, int frame_pos, int n_frames, int t_offset, int grid_h, int grid_w,
+                                int n_t, int n_h, int n_w, float theta, void* stream);
+
 /* nfd_kvcache_shift for the 8-bit caches: frames n_drop .. kv_frames-1 move to frames 0 .. ; same strategies
  * and errors (NFD_ERR_UNSUPPORTED for D != 64).  When T is a multiple of 16 whole key groups move (16-byte
  * vectors); otherwise V moves key by key through the handle's workspace, which must hold at least one feature

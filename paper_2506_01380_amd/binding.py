@@ -27,7 +27,7 @@ EXPORTS = (
     "nfd_rope_kvcache_append", "nfd_rope_check_args",
     "nfd_block_causal_attn_fwd_lse", "nfd_block_causal_attn_bwd",
     "nfd_kvcache_shift", "nfd_spec_init", "nfd_spec_next", "nfd_spec_accept", "nfd_attn_work_item",
-    "nfd_fp8_cache_bytes", "nfd_kvcache_append_fp8", "nfd_block_causal_attn_fwd_fp8kv", "nfd_kvcache_shift_fp8",
+    "nfd_fp8_cache_bytes", "nfd_kvcache_append_fp8", "nfd_block_causal_attn_fwd_fp8kv", "nfd_kvcache_shift_fp8", "nfd_rope_kvcache_append_fp8",
 )
 
 
@@ -111,6 +111,8 @@ def lib():
         L.nfd_fp8_cache_bytes.restype = ci
         L.nfd_kvcache_append_fp8.argtypes = [vp] * 7 + [ci] * 7 + [vp]
         L.nfd_kvcache_append_fp8.restype = ci
+        L.nfd_rope_kvcache_append_fp8.argtypes = [vp] * 9 + [ci] * 13 + [cf, vp]
+        L.nfd_rope_kvcache_append_fp8.restype = ci
         L.nfd_kvcache_shift_fp8.argtypes = [vp, vp, vp] + [ci] * 7 + [vp]
         L.nfd_kvcache_shift_fp8.restype = ci
         L.nfd_block_causal_attn_fwd_fp8kv.argtypes = [vp] * 7 + [ci] * 7 + [cf, vp]
@@ -206,6 +208,14 @@ def nfd_kvcache_append_fp8(h, k8, v8t, k_scale, v_scale, k_new, v_new, B, H, F, 
     rc = lib().nfd_kvcache_append_fp8(h, _addr(k8), _addr(v8t), _addr(k_scale), _addr(v_scale), _addr(k_new),
                                       _addr(v_new), B, H, F, T, D, frame_pos, n_frames, _stream(stream))
     _check(rc, "nfd_kvcache_append_fp8", h)
+
+
+def nfd_rope_kvcache_append_fp8(h, q, q_out, k8, v8t, k_scale, v_scale, k_new, v_new, B, H, F, T, D, frame_pos, n_frames,
+                                t_offset, grid_h, grid_w, n_t, n_h, n_w, theta=0.0, stream=None):
+    rc = lib().nfd_rope_kvcache_append_fp8(h, _addr(q), _addr(q_out), _addr(k8), _addr(v8t), _addr(k_scale), _addr(v_scale),
+                                           _addr(k_new), _addr(v_new), B, H, F, T, D, frame_pos, n_frames, t_offset,
+                                           grid_h, grid_w, n_t, n_h, n_w, theta, _stream(stream))
+    _check(rc, "nfd_rope_kvcache_append_fp8", h)
 
 
 def nfd_kvcache_shift_fp8(h, k8, v8t, B, H, F, T, D, kv_frames, n_drop, stream=None):

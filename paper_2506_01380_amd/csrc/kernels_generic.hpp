@@ -3,6 +3,7 @@
 // online softmax.  It is the fp32 path of the library and the fallback for head
 // widths the matrix-core kernel is not built for; it is not tuned.
 #pragma once
+#include "kernels_fp8.hpp"
 #include "nfd_common.hpp"
 
 namespace nfd {
@@ -290,10 +291,20 @@ struct RopeParams {
     int heads_per_thread;  // blockIdx.y selects a range of heads
 };
 
-template <typename E, int VEC>
+//
+// KV8 (bf16, VEC = 8 only): the caches are the 8-bit ones (kernels_fp8.hpp): the rotated key, rounded to bf16
+// exactly as for a bf16 cache, and the value are quantised with the head's scales; K codes go to 8 consecutive
+// bytes of the key's row, V codes to 8 feature rows at the key's (permuted) position.
+struct RopeFp8 {
+    const float* k_scale;  // [BH]
+    const float* v_scale;  // [BH]
+    int64_t Spad;          // keys per cache row set (F * T rounded up to 64)
+};
+
+template <typename E, int VEC, bool KV8 = false>
 __global__ void __launch_bounds__(256)
 rope_kvcache_append(const E* q, E* q_out, E* __restrict__ kc, E* __restrict__ vc,
-                    const E* __restrict__ kn, const E* __restrict__ vn, RopeParams rp, RopeTable tab) {
+                    const E* __restrict__ kn, const E* __restrict__ vn, RopeParams rp, RopeTable tab, RopeFp8 f8 = RopeFp8{}) {
     typedef __attribute__((ext_vector_type(VEC))) E vec_t;
     const int chunks = rp.D / VEC;
     const int64_t items = (int64_t)rp.n_frames * rp.T * chunks;
@@ -332,8 +343,24 @@ rope_kvcache_append(const E* q, E* q_out, E* __restrict__ kc, E* __restrict__ vc
             ko[2 * j + 1] = (E)(ka * sn[j] + kb * cs[j]);
         }
         *(vec_t*)(q_out + src) = qo;
-        *(vec_t*)(kc + dst) = ko;
-        *(vec_t*)(vc + dst) = vv;
+        if constexpr (KV8) {
+            static_assert(!KV8 || VEC == 8, "the 8-bit cache takes eight features per thread");
+            const float ik = __frcp_rn(f8.k_scale[bh]), iv = __frcp_rn(f8.v_scale[bh]);
+            const int64_t j = (int64_t)rp.frame_pos * rp.T + row;  // key index in the cache
+            uint32_t w0 = e4m3_pack2<false>((float)ko[0] * ik, (float)ko[1] * ik, 0u);
+            w0 = e4m3_pack2<true>((float)ko[2] * ik, (float)ko[3] * ik, w0);
+            uint32_t w1 = e4m3_pack2<false>((float)ko[4] * ik, (float)ko[5] * ik, 0u);
+            w1 = e4m3_pack2<true>((float)ko[6] * ik, (float)ko[7] * ik, w1);
+            const u32x2 w = {w0, w1};
+            *(u32x2*)((unsigned char*)kc + ((int64_t)bh * f8.Spad + j) * 64 + chunk * 8) = w;
+            unsigned char* vd = (unsigned char*)vc + ((int64_t)bh * 64 + chunk * 8) * f8.Spad + v8t_position(j, (chunk >> 1) & 1);
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                vd[(int64_t)e * f8.Spad] = (unsigned char)(e4m3_pack2<false>((float)vv[e] * iv, 0.f, 0u) & 0xffu);
+        } else {
+            *(vec_t*)(kc + dst) = ko;
+            *(vec_t*)(vc + dst) = vv;
+        }
     }
 }
 

@@ -13,7 +13,6 @@
 #include <new>
 #include <string>
 
-#include "kernels_fp8.hpp"
 #include "kernels_generic.hpp"
 #include "kernels_mfma.hpp"
 #include "kernels_mfma_bwd.hpp"
@@ -586,14 +585,23 @@ int nfd_rope_check_args(nfd_dtype_t dtype, int B, int H, int F, int T, int D, in
     return NFD_OK;
 }
 
-int nfd_rope_kvcache_append(nfd_attn_t* h, const void* q, void* q_out, void* k_cache, void* v_cache,
-                            const void* k_new, const void* v_new, int B, int H, int F, int T, int D,
-                            int frame_pos, int n_frames, int t_offset, int grid_h, int grid_w, int n_t,
-                            int n_h, int n_w, float theta, void* stream) {
+// k_scale / v_scale non-null: k_cache and v_cache are the 8-bit caches.
+static int rope_impl(nfd_attn_t* h, const void* q, void* q_out, void* k_cache, void* v_cache, const void* k_new,
+                     const void* v_new, int B, int H, int F, int T, int D, int frame_pos, int n_frames, int t_offset,
+                     int grid_h, int grid_w, int n_t, int n_h, int n_w, float theta, void* stream,
+                     const float* k_scale, const float* v_scale) {
     if (!h) return NFD_ERR_NULL;
     if (!q || !q_out || !k_cache || !v_cache || !k_new || !v_new) return fail(h, NFD_ERR_NULL, "tensors must be non-null");
     const int rc = nfd_rope_check_args(h->dtype, B, H, F, T, D, frame_pos, n_frames, grid_h, grid_w, n_t, n_h, n_w);
     if (rc != NFD_OK) return fail(h, rc, "invalid rotary-embedding arguments");
+    const bool kv8 = k_scale != nullptr;
+    if (kv8) {
+        if (h->dtype != NFD_BF16 || D != nfd::mfma::kD)
+            return fail(h, NFD_ERR_UNSUPPORTED, "the 8-bit cache is built for bf16 inputs and head width 64");
+        const uintptr_t any = (uintptr_t)q | (uintptr_t)q_out | (uintptr_t)k_cache | (uintptr_t)v_cache | (uintptr_t)k_new | (uintptr_t)v_new;
+        if (any % 16 != 0 || ((uintptr_t)k_scale | (uintptr_t)v_scale) % 4 != 0)
+            return fail(h, NFD_ERR_UNSUPPORTED, "tensors must be 16-byte aligned (scales 4-byte)");
+    }
     if (n_frames == 0) return NFD_OK;
     const double th = theta > 0.f ? (double)theta : 10000.0;
     nfd::RopeTable tab{};
@@ -629,22 +637,44 @@ int nfd_rope_kvcache_append(nfd_attn_t* h, const void* q, void* q_out, void* k_c
     const unsigned gy = (unsigned)((rp.BH + rp.heads_per_thread - 1) / rp.heads_per_thread);
     const dim3 grid((unsigned)gx, gy), block(256);
     hipStream_t st = (hipStream_t)stream;
-    if (h->dtype == NFD_BF16) {
+    const nfd::RopeFp8 f8{k_scale, v_scale, ((int64_t)F * T + 63) / 64 * 64};
+    if (kv8) {  // vec == 8 here: bf16, D = 64, all tensors 16-byte aligned
+        hipLaunchKernelGGL((nfd::rope_kvcache_append<__bf16, 8, true>), grid, block, 0, st, (const __bf16*)q, (__bf16*)q_out,
+                           (__bf16*)k_cache, (__bf16*)v_cache, (const __bf16*)k_new, (const __bf16*)v_new, rp, tab, f8);
+    } else if (h->dtype == NFD_BF16) {
         if (vec == 8)
-            hipLaunchKernelGGL((nfd::rope_kvcache_append<__bf16, 8>), grid, block, 0, st, (const __bf16*)q, (__bf16*)q_out,
-                               (__bf16*)k_cache, (__bf16*)v_cache, (const __bf16*)k_new, (const __bf16*)v_new, rp, tab);
+            hipLaunchKernelGGL((nfd::rope_kvcache_append<__bf16, 8, false>), grid, block, 0, st, (const __bf16*)q, (__bf16*)q_out,
+                               (__bf16*)k_cache, (__bf16*)v_cache, (const __bf16*)k_new, (const __bf16*)v_new, rp, tab, f8);
         else
-            hipLaunchKernelGGL((nfd::rope_kvcache_append<__bf16, 2>), grid, block, 0, st, (const __bf16*)q, (__bf16*)q_out,
-                               (__bf16*)k_cache, (__bf16*)v_cache, (const __bf16*)k_new, (const __bf16*)v_new, rp, tab);
+            hipLaunchKernelGGL((nfd::rope_kvcache_append<__bf16, 2, false>), grid, block, 0, st, (const __bf16*)q, (__bf16*)q_out,
+                               (__bf16*)k_cache, (__bf16*)v_cache, (const __bf16*)k_new, (const __bf16*)v_new, rp, tab, f8);
     } else {
         if (vec == 4)
-            hipLaunchKernelGGL((nfd::rope_kvcache_append<float, 4>), grid, block, 0, st, (const float*)q, (float*)q_out,
-                               (float*)k_cache, (float*)v_cache, (const float*)k_new, (const float*)v_new, rp, tab);
+            hipLaunchKernelGGL((nfd::rope_kvcache_append<float, 4, false>), grid, block, 0, st, (const float*)q, (float*)q_out,
+                               (float*)k_cache, (float*)v_cache, (const float*)k_new, (const float*)v_new, rp, tab, f8);
         else
-            hipLaunchKernelGGL((nfd::rope_kvcache_append<float, 2>), grid, block, 0, st, (const float*)q, (float*)q_out,
-                               (float*)k_cache, (float*)v_cache, (const float*)k_new, (const float*)v_new, rp, tab);
+            hipLaunchKernelGGL((nfd::rope_kvcache_append<float, 2, false>), grid, block, 0, st, (const float*)q, (float*)q_out,
+                               (float*)k_cache, (float*)v_cache, (const float*)k_new, (const float*)v_new, rp, tab, f8);
     }
     return check_hip(h, hipGetLastError(), "rotary embedding launch");
+}
+
+int nfd_rope_kvcache_append(nfd_attn_t* h, const void* q, void* q_out, void* k_cache, void* v_cache,
+                            const void* k_new, const void* v_new, int B, int H, int F, int T, int D,
+                            int frame_pos, int n_frames, int t_offset, int grid_h, int grid_w, int n_t,
+                            int n_h, int n_w, float theta, void* stream) {
+    return rope_impl(h, q, q_out, k_cache, v_cache, k_new, v_new, B, H, F, T, D, frame_pos, n_frames, t_offset, grid_h,
+                     grid_w, n_t, n_h, n_w, theta, stream, nullptr, nullptr);
+}
+
+int nfd_rope_kvcache_append_fp8(nfd_attn_t* h, const void* q, void* q_out, void* k8, void* v8t, const float* k_scale,
+                                const float* v_scale, const void* k_new, const void* v_new, int B, int H, int F,
+                                int T, int D, int frame_pos, int n_frames, int t_offset, int grid_h, int grid_w,
+                                int n_t, int n_h, int n_w, float theta, void* stream) {
+    if (!h) return NFD_ERR_NULL;
+    if (!k_scale || !v_scale) return fail(h, NFD_ERR_NULL, "k_scale and v_scale must be non-null");
+    return rope_impl(h, q, q_out, k8, v8t, k_new, v_new, B, H, F, T, D, frame_pos, n_frames, t_offset, grid_h, grid_w,
+                     n_t, n_h, n_w, theta, stream, k_scale, v_scale);
 }
 
 }  // extern "C"

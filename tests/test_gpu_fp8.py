@@ -310,3 +310,43 @@ def test_speculative_decode_loop_over_the_8bit_cache(T):
         assert n_steps == len(expect) and s.done == total
     finally:
         a.close()
+
+
+@pytest.mark.parametrize("B,H,grid,F,pos,n", [(1, 2, (6, 8), 5, 1, 2), (2, 3, (5, 7), 4, 0, 3), (1, 16, (24, 14), 3, 2, 1)])
+def test_fused_rotary_and_quantising_append(attn, B, H, grid, F, pos, n):
+    """One call (rotate q and k, quantise k and v into the 8-bit caches) against the two calls it replaces: rotary
+    pre-op into a bf16 buffer, then the quantising append - identical codes and identical rotated queries, and
+    untouched bytes everywhere else.  The two-call path is itself checked against the oracle: rotated keys within
+    one bf16 step, and the codes the oracle's quantiser gives for the device's rotated keys, bit for bit."""
+    from oracle import nfd_oracle as orc
+    D, sections = 64, (16, 24, 24)
+    T = grid[0] * grid[1]
+    rng = np.random.default_rng(900 + T)
+    qn, kn, vn = (wl.round_to_bf16(rng.standard_normal((B, H, n * T, D)).astype(np.float32)) for _ in range(3))
+    ks, vs = _scales(B, H, T, 0.01, 0.03)
+    ksd, vsd = torch.from_numpy(ks).cuda(), torch.from_numpy(vs).cuda()
+    qd, kd, vd = _bf16(qn), _bf16(kn), _bf16(vn)
+    # two calls
+    kt = torch.zeros((B, H, n * T, D), dtype=torch.bfloat16, device="cuda")
+    vt = torch.zeros_like(kt)
+    q_two = attn.rope_append(qd, kt, vt, kd, vd, T, 0, grid, sections, t_offset=pos)  # temporal position = pos + frame
+    k8a, v8a = _caches(B, H, F, T)
+    nb.nfd_kvcache_append_fp8(attn.h, k8a, v8a, ksd, vsd, kt, vt, B, H, F, T, D, pos, n)
+    # one call
+    k8b, v8b = _caches(B, H, F, T)
+    q_one = torch.empty_like(qd)
+    nb.nfd_rope_kvcache_append_fp8(attn.h, qd, q_one, k8b, v8b, ksd, vsd, kd, vd, B, H, F, T, D, pos, n, 0,
+                                   grid[0], grid[1], sections[0], sections[1], sections[2])
+    torch.cuda.synchronize()
+    assert torch.equal(q_one, q_two)
+    assert torch.equal(k8a, k8b) and torch.equal(v8a, v8b)
+    # the two-call path against the oracle
+    zeros = np.zeros((B, H, n * T, D))
+    rq, rk, rv = orc.rope_kvcache_append(qn, zeros, zeros.copy(), kn, vn, T, 0, grid, sections, t_offset=pos)
+    dk = kt.float().cpu().numpy().astype(np.float64)
+    assert np.all(np.abs(dk - rk) <= np.abs(rk) * 2.0 ** -8 + 1e-6)
+    gk, gv = _host_views(k8b, v8b, B, H, F, T)
+    assert np.array_equal(gk[:, :, pos * T:(pos + n) * T], f8.quantize(dk, ks[:, :, None, None]))
+    assert np.array_equal(gv[:, :, :, pos * T:(pos + n) * T], np.swapaxes(f8.quantize(vn, vs[:, :, None, None]), 2, 3))
+    assert np.all(gk[:, :, :pos * T] == NAN_CODE) and np.all(gk[:, :, (pos + n) * T:] == NAN_CODE)
+    assert np.all(gv[:, :, :, :pos * T] == NAN_CODE) and np.all(gv[:, :, :, (pos + n) * T:] == NAN_CODE)
