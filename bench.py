@@ -309,8 +309,14 @@ def main():
             dt, fl, n = run_rows(wl.sample_rows(T, qf, per_frame, cfg["seed"]))
             what = "%d of %d query rows per head (first, last and %d random rows of each frame), all %d heads" % (
                 n, qf * T, per_frame, B * H)
+        model = "unknown"
+        try:
+            with open("/proc/cpuinfo") as f:
+                model = next((l.split(":", 1)[1].strip() for l in f if l.startswith("model name")), "unknown")
+        except OSError:
+            pass
         cpu = dict(value=round(fl / dt * 1e-12, 5), unit="TFLOP/s", cores=cores, kind="oracle",
-                   sample="%s, %.1f s of oracle time" % (what, dt))
+                   sample="%s, %.1f s of oracle time" % (what, dt), cpu=model)
 
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
