@@ -280,13 +280,12 @@ def main():
                           if k in ("workload", "ms_per_step", "ms_median", "ms_min", "tflops", "frames_per_s")})
             print(json.dumps({"fp8_kv_cache": fp8kv[-1]}), file=sys.stderr, flush=True)
 
-    cpu = None
-    if not args.no_cpu_baseline:
+    def oracle_rate(name, seconds):
+        """The fp64 oracle on the host cores on a bounded sample of the workload (whole rows, all heads)."""
         from oracle import nfd_oracle as orc
-        B, H, D, T, kvf, qf = (cfg[x] for x in ("B", "H", "D", "T", "kv_frames", "q_frames"))
-        _, q, k, v = wl.make_config(args.workload)
+        c, q, k, v = wl.make_config(name)
+        B, H, D, T, kvf, qf = (c[x] for x in ("B", "H", "D", "T", "kv_frames", "q_frames"))
         cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
-
         q64, k64, v64 = (np.asarray(x, dtype=np.float64) for x in (q, k, v))  # exact widening, outside the timed part
         P = kvf - qf
 
@@ -298,15 +297,15 @@ def main():
             pairs = int(sum((P + int(r) // T + 1) * T for r in idx)) * B * H
             return dt, 4 * D * pairs, len(idx)
 
-        # calibrate on two rows per frame, then size the sample for about --cpu-seconds of oracle time
-        dt0, fl0, n0 = run_rows(wl.sample_rows(T, qf, 0, cfg["seed"]))
-        rows_fit = int(n0 * args.cpu_seconds / max(dt0, 1e-4))
+        # calibrate on two rows per frame, then size the sample for about `seconds` of oracle time
+        dt0, fl0, n0 = run_rows(wl.sample_rows(T, qf, 0, c["seed"]))
+        rows_fit = int(n0 * seconds / max(dt0, 1e-4))
         if rows_fit >= qf * T:
             dt, fl, n = run_rows(None)
             what = "all %d query rows of all %d heads (the whole workload)" % (qf * T, B * H)
         else:
             per_frame = max(1, rows_fit // qf - 2)
-            dt, fl, n = run_rows(wl.sample_rows(T, qf, per_frame, cfg["seed"]))
+            dt, fl, n = run_rows(wl.sample_rows(T, qf, per_frame, c["seed"]))
             what = "%d of %d query rows per head (first, last and %d random rows of each frame), all %d heads" % (
                 n, qf * T, per_frame, B * H)
         model = "unknown"
@@ -315,8 +314,15 @@ def main():
                 model = next((l.split(":", 1)[1].strip() for l in f if l.startswith("model name")), "unknown")
         except OSError:
             pass
-        cpu = dict(value=round(fl / dt * 1e-12, 5), unit="TFLOP/s", cores=cores, kind="oracle",
-                   sample="%s, %.1f s of oracle time" % (what, dt), cpu=model)
+        return dict(value=round(fl / dt * 1e-12, 5), unit="TFLOP/s", cores=cores, kind="oracle",
+                    sample="%s, %.1f s of oracle time" % (what, dt), cpu=model)
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = oracle_rate(args.workload, args.cpu_seconds)
+        for r in others:  # --all: the oracle beside every GPU time, a few seconds each
+            r["cpu_baseline"] = oracle_rate(r["workload"], min(args.cpu_seconds, 4.0))
+            print(json.dumps({"workload": r["workload"], "cpu_baseline": r["cpu_baseline"]}), file=sys.stderr, flush=True)
 
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
@@ -350,7 +356,8 @@ def main():
         line["fp8_kv_cache"] = fp8kv
     if others:
         line["other_workloads"] = [{k: (round(v, 4) if isinstance(v, float) else v) for k, v in r.items()
-                                    if k in ("workload", "ms_per_step", "ms_median", "ms_min", "tflops", "gbs", "frames_per_s")} for r in others]
+                                    if k in ("workload", "ms_per_step", "ms_median", "ms_min", "tflops", "gbs", "frames_per_s", "cpu_baseline")}
+                                   for r in others]
     attn.close()
     print(json.dumps(line), flush=True)
 
