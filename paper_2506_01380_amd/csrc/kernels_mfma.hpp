@@ -149,7 +149,7 @@ __device__ __forceinline__ WorkItem decode_work(const FwdParams& p) {
 }
 
 // Final write of one wavefront's 64 query rows: normalised bf16 output when the keys were not
-// split, otherwise the unnormalised fp32 accumulator plus (reference max in log2 units, row sum).
+// split, otherwise the unnormalised accumulator (bf16) plus (reference max in log2 units, row sum; fp32).
 // Lane (n, h) holds, for query column n of block qt, output features 32*dt + 8*rb + 4*h + 0..3.
 template <int QT>
 __device__ __forceinline__ void store_rows(const FwdParams& p, const WorkItem& wi, const int (&row)[QT], int h,
@@ -174,14 +174,14 @@ __device__ __forceinline__ void store_rows(const FwdParams& p, const WorkItem& w
             if (p.lse && h == 0) p.lse[(int64_t)wi.bh * p.Sq + row[qt]] = (m_used[qt] * c + __builtin_log2f(l_row)) * kLn2;
         } else {
             const int64_t prow = ((int64_t)wi.bh * p.n_splits + wi.split) * p.Sq + row[qt];
-            float* po = p.part_o + prow * kD;
+            __bf16* po = p.part_o + prow * kD;
 #pragma unroll
             for (int dt = 0; dt < 2; ++dt)
 #pragma unroll
                 for (int rb = 0; rb < 4; ++rb) {
                     const f32x4 x = {o_acc[dt][qt][4 * rb], o_acc[dt][qt][4 * rb + 1], o_acc[dt][qt][4 * rb + 2],
                                      o_acc[dt][qt][4 * rb + 3]};
-                    *(f32x4*)(po + 32 * dt + 8 * rb + 4 * h) = x;
+                    *(bf16x4*)(po + 32 * dt + 8 * rb + 4 * h) = __builtin_convertvector(x, bf16x4);
                 }
             if (h == 0) {
                 const f32x2 ml = {m_used[qt] * c, l_row};
@@ -638,12 +638,12 @@ attn_combine_d64(FwdParams p) {
     f32x4 acc = {0.f, 0.f, 0.f, 0.f};
     for (int s0 = 0; s0 < p.n_splits; s0 += U) {
         f32x2 ml[U];
-        f32x4 o[U];
+        bf16x4 o[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int64_t prow = prow0 + (int64_t)min(s0 + u, p.n_splits - 1) * p.Sq;  // clamped: dropped below
             ml[u] = *(const f32x2*)(p.part_ml + prow * 2);
-            o[u] = *(const f32x4*)(p.part_o + prow * kD + 4 * dq);
+            o[u] = *(const bf16x4*)(p.part_o + prow * kD + 4 * dq);
         }
         float m_new = m_run;
 #pragma unroll
@@ -658,7 +658,7 @@ attn_combine_d64(FwdParams p) {
             if (s0 + u < p.n_splits) {
                 const float w = __builtin_amdgcn_exp2f(ml[u][0] - m_new);
                 l += w * ml[u][1];
-                acc += w * o[u];
+                acc += w * __builtin_convertvector(o[u], f32x4);
             }
     }
     const float inv = 1.0f / l;

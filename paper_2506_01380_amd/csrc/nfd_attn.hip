@@ -29,6 +29,8 @@ struct nfd_attn {
 namespace {
 
 constexpr size_t kDefaultWorkspace = (size_t)128 << 20;
+// one row of one key split in the workspace: 64 bf16 partial outputs + (max, sum) in fp32
+constexpr size_t kPartialRowBytes = nfd::mfma::kD * 2 + 2 * sizeof(float);
 
 int fail(nfd_attn_t* h, int code, const std::string& msg) {
     if (h) h->err = msg;
@@ -119,7 +121,7 @@ int nfd_attn_plan(nfd_dtype_t dtype, int B, int H, int F, int T, int D, int kv_f
         const int64_t slots = (int64_t)num_cus * wg_per_cu, base = BH * pl.n_q_tiles;
         int splits = 1;
         if (base < slots) {
-            const size_t per_split = (size_t)(BH * Sq) * (nfd::mfma::kD + 2) * sizeof(float);
+            const size_t per_split = (size_t)(BH * Sq) * kPartialRowBytes;
             double best = 1e30;
             for (int s = 1; s <= 64 && s <= std::max<int64_t>(1, max_tiles / 2); ++s) {
                 if (s > 1 && per_split * s > workspace_limit) break;
@@ -134,7 +136,7 @@ int nfd_attn_plan(nfd_dtype_t dtype, int B, int H, int F, int T, int D, int kv_f
         }
 #ifdef NFD_TUNE_SPLITS  // development build: sweep the split count from the environment
         if (const char* e = getenv("NFD_SPLITS")) {
-            const size_t per_split = (size_t)(BH * Sq) * (nfd::mfma::kD + 2) * sizeof(float);
+            const size_t per_split = (size_t)(BH * Sq) * kPartialRowBytes;
             splits = std::max(1, std::min(atoi(e), (int)std::max<int64_t>(1, max_tiles / 2)));
             while (splits > 1 && per_split * splits > workspace_limit) --splits;  // never beyond the workspace
         }
@@ -144,7 +146,7 @@ int nfd_attn_plan(nfd_dtype_t dtype, int B, int H, int F, int T, int D, int kv_f
         pl.n_workgroups = (int)(BH * pl.n_q_tiles * splits);
         pl.key_tiles_visited = visited * BH;
         pl.key_tiles_dense = (int64_t)pl.n_q_tiles * (((int64_t)kv_frames * T + pl.block_n - 1) / pl.block_n) * BH;
-        pl.workspace_bytes = splits > 1 ? (size_t)(BH * Sq) * splits * (nfd::mfma::kD + 2) * sizeof(float) : 0;
+        pl.workspace_bytes = splits > 1 ? (size_t)(BH * Sq) * splits * kPartialRowBytes : 0;
     } else {
         pl.kernel = 0;
         pl.block_m = nfd::kGenericWaves;  // one row per wavefront
@@ -256,8 +258,8 @@ static int fwd_impl(nfd_attn_t* h, const void* q, const void* k, const void* v, 
     p.group_q_tiles = pl.n_splits > 1 && (double)p.BH * p.Sk * nfd::mfma::kD * 2.0 * (kv8 ? 1.0 : 2.0) > 192e6;
     p.scale_log2e = scale * nfd::kLog2e;
     if (pl.n_splits > 1) {
-        p.part_o = (float*)h->workspace;
-        p.part_ml = p.part_o + (size_t)p.BH * pl.n_splits * p.Sq * nfd::mfma::kD;
+        p.part_o = (__bf16*)h->workspace;
+        p.part_ml = (float*)(p.part_o + (size_t)p.BH * pl.n_splits * p.Sq * nfd::mfma::kD);
     }
     hipStream_t st = (hipStream_t)stream;
 

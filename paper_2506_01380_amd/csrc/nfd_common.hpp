@@ -28,7 +28,8 @@ struct FwdParams {
     const void* k;      // [BH, Scap, D]
     const void* v;      // [BH, Scap, D]
     void* out;          // [BH, Sq, D]
-    float* part_o;      // [BH, n_splits, Sq, D] un-normalised partial outputs (split launches)
+    __bf16* part_o;     // [BH, n_splits, Sq, D] un-normalised partial outputs (split launches), rounded to bf16:
+                        // one more rounding of the kind the output gets anyway, for half the combine's traffic
     float* part_ml;     // [BH, n_splits, Sq, 2]  (running max in log2 units, running sum)
     float* lse;         // [BH, Sq] optional: natural log of the row's softmax denominator (for the backward)
     int BH;             // B * H

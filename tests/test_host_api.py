@@ -76,8 +76,8 @@ def test_plan_training_form_skips_future_tiles():
 def test_plan_cached_forms_split_keys_and_fit_workspace():
     pl = nb.nfd_attn_plan(nb.NFD_BF16, 1, 16, 40, 336, 64, 33, 1)
     assert pl["n_splits"] > 1 and pl["workspace_bytes"] <= 128 << 20
-    assert pl["workspace_bytes"] == 16 * 336 * pl["n_splits"] * 66 * 4
-    small = nb.nfd_attn_plan(nb.NFD_BF16, 1, 16, 40, 336, 64, 33, 1, 256, 3 * 16 * 336 * 66 * 4)
+    assert pl["workspace_bytes"] == 16 * 336 * pl["n_splits"] * (64 * 2 + 8)
+    small = nb.nfd_attn_plan(nb.NFD_BF16, 1, 16, 40, 336, 64, 33, 1, 256, 3 * 16 * 336 * (64 * 2 + 8))
     assert small["n_splits"] == 3
     none = nb.nfd_attn_plan(nb.NFD_BF16, 1, 16, 40, 336, 64, 33, 1, 256, 1000)
     assert none["n_splits"] == 1 and none["workspace_bytes"] == 0
