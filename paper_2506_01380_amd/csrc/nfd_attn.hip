@@ -117,7 +117,7 @@ int nfd_attn_plan(nfd_dtype_t dtype, int B, int H, int F, int T, int D, int kv_f
         // two workgroups share a CU: workgroups run in rounds of 2 per CU; a workgroup that has its CU
         // to itself is about 1.2x faster (measured); every workgroup pays a fixed prologue/epilogue of
         // about three tiles; the combine pass costs a launch plus the write and read of the partials,
-        // which grows with rows x splits (about one unit per 15000 row-partials at HBM speed).
+        // which grows with rows x splits (about one unit per 30000 row-partials of 136 bytes at HBM speed).
         const int64_t slots = (int64_t)num_cus * wg_per_cu, base = BH * pl.n_q_tiles;
         int splits = 1;
         if (base < slots) {
@@ -129,7 +129,7 @@ int nfd_attn_plan(nfd_dtype_t dtype, int B, int H, int F, int T, int D, int kv_f
                 const int64_t rounds = (wgs + slots - 1) / slots;
                 const double len = (double)((max_tiles + s - 1) / s) + 3.0;
                 const double pace = wgs * 2 <= slots ? 0.83 : 1.0;
-                const double combine = s > 1 ? 1.0 + (double)s * (double)(BH * Sq) / 15000.0 : 0.0;
+                const double combine = s > 1 ? 1.0 + (double)s * (double)(BH * Sq) / 30000.0 : 0.0;
                 const double cost = rounds * len * pace + combine;
                 if (cost < best) { best = cost; splits = s; }
             }
