@@ -4,9 +4,9 @@
 // attention, Sec. 3.2).  With p_ij = exp(s_ij - lse_i) the softmax weights of the visible keys,
 //   dv_j = sum_i p_ij do_i            dp_ij = <do_i, v_j>         delta_i = <do_i, o_i> = sum_j p_ij dp_ij
 //   ds_ij = p_ij (dp_ij - delta_i)    dq_i = scale sum_j ds_ij k_j    dk_j = scale sum_i ds_ij q_i
-// Three launches, no atomics, bit-reproducible:
-//   attn_bwd_delta         delta_i = <do_i, o_i>                                   (streaming)
-//   attn_bwd_dq_bf16_d64   query-major, same decomposition and tile ring as the forward kernel
+// Two launches, no atomics, bit-reproducible:
+//   attn_bwd_dq_bf16_d64   query-major, same decomposition and tile ring as the forward kernel; it also forms
+//                          delta_i = <do_i, o_i> of its rows (dout is in its registers anyway) and stores it
 //   attn_bwd_dkdv_bf16_d64 key-major: a wavefront owns 32 (or 64) keys and walks over the query tiles that see them
 // Both matrix kernels recompute the weights from the stored log-sum-exp, so no online softmax is
 // needed, and both keep the operand whose rows they own in registers for the whole kernel.  Tiles
@@ -29,8 +29,9 @@ struct BwdParams {
     const void* k;       // [BH, Scap, D]
     const void* v;       // [BH, Scap, D]
     const void* dout;    // [BH, Sq, D]
+    const void* out;     // [BH, Sq, D] the forward's result
     const float* lse;    // [BH, Sq] natural log of the softmax denominator (from the forward call)
-    float* delta;        // [BH, Sq] <dout_i, out_i> (workspace)
+    float* delta;        // [BH, Sq] <dout_i, out_i> (workspace): written by the dq kernel, read by the dk/dv kernel
     void* dq;            // [BH, Sq, D]
     void* dk;            // [BH, Scap, D], rows < Sk written
     void* dv;            // [BH, Scap, D], rows < Sk written
@@ -40,25 +41,6 @@ struct BwdParams {
     float scale;
     float scale_log2e;
 };
-
-// delta_i = <dout_i, out_i>: eight lanes per row, 16 bytes each.
-__global__ void __launch_bounds__(256)
-attn_bwd_delta(const __bf16* __restrict__ out, const __bf16* __restrict__ dout, float* __restrict__ delta,
-               int64_t rows) {
-    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const int64_t row = idx >> 3;
-    float s = 0.f;
-    if (row < rows) {
-        const bf16x8 a = *(const bf16x8*)(out + idx * 8);
-        const bf16x8 b = *(const bf16x8*)(dout + idx * 8);
-#pragma unroll
-        for (int e = 0; e < 8; ++e) s += (float)a[e] * (float)b[e];
-    }
-    s += __shfl_xor(s, 1);
-    s += __shfl_xor(s, 2);
-    s += __shfl_xor(s, 4);
-    if (row < rows && (idx & 7) == 0) delta[row] = s;
-}
 
 // Workgroup id -> (head, item): ids are dealt round-robin to the 8 XCDs; when the head count is a
 // multiple of 8 heads are pinned to an XCD (bh % 8), otherwise ids run plainly over the heads; either
@@ -159,6 +141,7 @@ attn_bwd_dq_bf16_d64(BwdParams p) {
 
     const __bf16* qg = (const __bf16*)p.q + (int64_t)wi.bh * p.Sq * kD;
     const __bf16* gg = (const __bf16*)p.dout + (int64_t)wi.bh * p.Sq * kD;
+    const __bf16* og_ = (const __bf16*)p.out + (int64_t)wi.bh * p.Sq * kD;
     const __bf16* kg = (const __bf16*)p.k + (int64_t)wi.bh * p.Scap * kD;
     const __bf16* vg = (const __bf16*)p.v + (int64_t)wi.bh * p.Scap * kD;
 
@@ -172,12 +155,17 @@ attn_bwd_dq_bf16_d64(BwdParams p) {
         const int rc = min(row[qt], p.Sq - 1);  // ragged tail: compute a duplicate, never store it
         kmax_lane[qt] = kmax_of_row(rc, p.T, p.P);
         lse2[qt] = p.lse[(int64_t)wi.bh * p.Sq + rc] * kLog2e;
-        dl[qt] = p.delta[(int64_t)wi.bh * p.Sq + rc];
+        float part = 0.f;  // this lane's half of <dout_i, out_i>: the features it holds of dout
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
             qf[qt][ks] = *(const bf16x8*)(qg + (int64_t)rc * kD + 16 * ks + 8 * h);
             gf[qt][ks] = *(const bf16x8*)(gg + (int64_t)rc * kD + 16 * ks + 8 * h);
+            const bf16x8 of = *(const bf16x8*)(og_ + (int64_t)rc * kD + 16 * ks + 8 * h);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) part = __builtin_fmaf((float)gf[qt][ks][e], (float)of[e], part);
         }
+        dl[qt] = part + __shfl_xor(part, 32);
+        if (h == 0 && row[qt] < p.Sq) p.delta[(int64_t)wi.bh * p.Sq + row[qt]] = dl[qt];  // for the dk/dv kernel
     }
     const int kmin_wave = kmax_of_row(min(rw0, p.Sq - 1), p.T, p.P);
     const int kmax_wave = kmax_of_row(min(rw0 + 63, p.Sq - 1), p.T, p.P);

@@ -390,7 +390,7 @@ int nfd_block_causal_attn_bwd(nfd_attn_t* h, const void* q, const void* k, const
     if (!(scale > 0.f)) scale = 1.0f / std::sqrt((float)D);
 
     nfd::mfma::BwdParams p{};
-    p.q = q; p.k = k; p.v = v; p.dout = dout; p.lse = lse;
+    p.q = q; p.k = k; p.v = v; p.dout = dout; p.out = out; p.lse = lse;
     p.delta = (float*)h->workspace;
     p.dq = dq; p.dk = dk; p.dv = dv;
     p.BH = (int)BH; p.Sq = (int)Sq; p.Sk = (int)Sk; p.Scap = F * T; p.T = T; p.P = kv_frames - q_frames;
@@ -400,12 +400,10 @@ int nfd_block_causal_attn_bwd(nfd_attn_t* h, const void* q, const void* k, const
     p.scale = scale;
     p.scale_log2e = scale * nfd::kLog2e;
     hipStream_t st = (hipStream_t)stream;
-    const int64_t rows = BH * Sq;
     const unsigned heads8 = (unsigned)BH;  // one workgroup per (head, item)
-    hipLaunchKernelGGL(nfd::mfma::attn_bwd_delta, dim3((unsigned)((rows * 8 + 255) / 256)), dim3(256), 0, st,
-                       (const __bf16*)out, (const __bf16*)dout, p.delta, rows);
-    hipLaunchKernelGGL(nfd::mfma::attn_bwd_dkdv_bf16_d64<kKeysPerWave / 32>, dim3(heads8 * p.n_k_blocks), dim3(256), 0, st, p);
+    // the dq kernel first: it writes the per-row delta that the dk/dv kernel reads
     hipLaunchKernelGGL(nfd::mfma::attn_bwd_dq_bf16_d64, dim3(heads8 * p.n_q_tiles), dim3(256), 0, st, p);
+    hipLaunchKernelGGL(nfd::mfma::attn_bwd_dkdv_bf16_d64<kKeysPerWave / 32>, dim3(heads8 * p.n_k_blocks), dim3(256), 0, st, p);
     return check_hip(h, hipGetLastError(), "backward launch");
 }
 
