@@ -179,7 +179,7 @@ def main():
                     gbs=round(nbytes / ms * 1e-6, 1), frac_hbm_peak=round(nbytes / ms * 1e-6 / PEAK_HBM_GBS, 4))
 
     def time_bwd(name, steps, warmup):
-        """Forward that keeps the log-sum-exp, then the backward (delta, dk/dv, dq kernels).  FLOPs counted:
+        """Forward that keeps the log-sum-exp, then the backward (dq kernel, then dk/dv kernel).  FLOPs counted:
         forward 4.D per visible pair, backward 10.D (five products), the recomputation in the second
         backward kernel is not counted."""
         c = wl.CONFIGS[name]
@@ -212,7 +212,7 @@ def main():
         fwd()
         ms_f, ms_b = timed(fwd), timed(bwd)
         fl = nb.unmasked_flops(B, H, D, T, kvf, qf)
-        return dict(kernel="attn_bwd_dkdv_bf16_d64 + attn_bwd_dq_bf16_d64 + attn_bwd_delta", workload=name,
+        return dict(kernel="attn_bwd_dq_bf16_d64 + attn_bwd_dkdv_bf16_d64", workload=name,
                     fwd_lse_ms=round(ms_f, 5), bwd_ms=round(ms_b, 5), bwd_tflops=round(2.5 * fl / ms_b * 1e-9, 2),
                     bwd_frac_mfma_peak=round(2.5 * fl / ms_b * 1e-9 / PEAK_BF16_TFLOPS, 4),
                     fwd_bwd_tflops=round(3.5 * fl / (ms_f + ms_b) * 1e-9, 2))
