@@ -229,16 +229,22 @@ def main():
         cus = torch.cuda.get_device_properties(0).multi_processor_count
         iters = 60000  # 35-80 ms per mode: long enough for the clock to settle under the power limit
         ceiling = {"workgroups": cus, "iters": iters, "modes": {}}
-        for mode, gauss, nm in ((0, 0, "mfma_only_narrow_operands"), (0, 1, "mfma_only"), (1, 1, "vector_only"),
-                                (2, 1, "sequential"), (3, 1, "interleaved_1_to_7"), (3, 0, "interleaved_narrow_operands")):
+        # the last two modes launch two workgroups per CU: two wavefronts per SIMD, as in the attention kernel
+        for mode, gauss, wpc, nm in ((0, 0, 1, "mfma_only_narrow_operands"), (0, 1, 1, "mfma_only"), (1, 1, 1, "vector_only"),
+                                     (2, 1, 1, "sequential"), (3, 1, 1, "interleaved_1_to_7"),
+                                     (3, 0, 1, "interleaved_narrow_operands"), (2, 1, 2, "sequential_two_per_simd"),
+                                     (3, 1, 2, "interleaved_two_per_simd")):
             ms, cyc = ctypes.c_float(0), ctypes.c_double(0)
-            rc = P.nfd_probe_issue_mix(mode, cus, iters, gauss, ctypes.byref(ms), ctypes.byref(cyc))
+            n_it = iters // wpc
+            rc = P.nfd_probe_issue_mix(mode, cus * wpc, n_it, gauss, ctypes.byref(ms), ctypes.byref(cyc))
             if rc != 0:
                 raise SystemExit("issue-mix probe failed with code %d" % rc)
             # per iteration and wavefront: 32 MFMA of 32x32x16 = 1.049 MFLOP (not in the vector-only mode)
-            fl = 0.0 if mode == 1 else 32 * 2 * 32 * 32 * 16 * 4.0 * cus * iters
-            ceiling["modes"][nm] = {"cycles_per_tile": round(cyc.value, 1), "ms": round(ms.value, 4),
-                                    "mhz": round(cyc.value * iters / (ms.value * 1e3), 0),
+            fl = 0.0 if mode == 1 else 32 * 2 * 32 * 32 * 16 * 4.0 * cus * wpc * n_it
+            # cycles per wave-tile and the clock they imply are given for one wavefront per SIMD only: with two, the
+            # counter of one wavefront no longer measures the SIMD's time per tile
+            ceiling["modes"][nm] = {"cycles_per_tile": round(cyc.value, 1) if wpc == 1 else None, "ms": round(ms.value, 4),
+                                    "mhz": round(cyc.value * n_it / (ms.value * 1e3), 0) if wpc == 1 else None,
                                     "tflops": round(fl / ms.value * 1e-9, 1)}
         print(json.dumps({"issue_mix_ceiling": ceiling}), file=sys.stderr, flush=True)
 

@@ -17,8 +17,10 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
 
 // MODE 0: MFMA only; 1: vector only; 2: both, one after the other; 3: both, interleaved 1 : 7
+// At most 256 registers per lane, so that two workgroups fit a CU: launched with twice as many workgroups as
+// CUs, every SIMD holds two wavefronts, as in the attention kernel.
 template <int MODE>
-__global__ void __launch_bounds__(256, 1)
+__global__ void __launch_bounds__(256, 2)
 issue_mix(float* out, const u32x4* in, int iters, float c, unsigned long long* cycles) {
     bf16x8 a[8], b[8];
     for (int j = 0; j < 8; ++j) {
@@ -131,7 +133,8 @@ static int run_mode(int workgroups, int iters, int gaussian, float* ms, double* 
     return rc;
 }
 
-// mode 0..3 as above, gaussian as in fill_operands; one workgroup of 4 wavefronts per CU when workgroups == number of CUs.
+// mode 0..3 as above, gaussian as in fill_operands; one wavefront per SIMD when workgroups == number of CUs, two when
+// workgroups == twice that.
 // Returns 0, -5 on a HIP error, -6 on allocation failure, -2 on a bad mode.
 extern "C" int nfd_probe_issue_mix(int mode, int workgroups, int iters, int gaussian, float* ms, double* cycles_per_iter) {
     if (!ms || !cycles_per_iter || workgroups < 1 || iters < 1) return -2;
