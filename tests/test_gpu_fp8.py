@@ -4,6 +4,7 @@ stand for (same bound as the bf16 cache: the codes widen to bf16 exactly, so the
 operands is the bf16 kernel's)."""
 import numpy as np
 import pytest
+from parity_bounds import BF16_ROW_REL_L2, worst_row
 import torch
 
 from oracle import fp8_cache as f8
@@ -140,6 +141,8 @@ def _check(got, ref, tag):
     mx, rel = float(np.abs(d).max()), float(np.linalg.norm(d) / np.linalg.norm(ref))
     print("%s: max_abs=%.3e rel_l2=%.3e" % (tag, mx, rel), flush=True)
     assert mx <= TOL_MAX_ABS and rel <= TOL_REL_L2, (tag, mx, rel)
+    worst, where = worst_row(got, ref)
+    assert worst <= BF16_ROW_REL_L2, (tag, worst, where)
 
 
 CASES = [

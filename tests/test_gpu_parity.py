@@ -12,8 +12,7 @@ from paper_2506_01380_amd import workloads as wl
 
 pytestmark = pytest.mark.gpu
 
-BF16_MAX_ABS, BF16_REL_L2, FP32_MAX_ABS = 2e-2, 1e-2, 1e-4
-BF16_REL_L2_INTERNAL = 5e-3
+from parity_bounds import (BF16_MAX_ABS, BF16_REL_L2, BF16_REL_L2_INTERNAL, BF16_ROW_REL_L2, FP32_MAX_ABS, worst_row)
 
 
 @pytest.fixture(scope="module")
@@ -46,12 +45,14 @@ def errors(got, ref):
     return float(np.abs(d).max()), float(np.linalg.norm(d) / np.linalg.norm(ref))
 
 
-def check_bf16(got, ref, tag):
+def check_bf16(got, ref, tag, row_bound=BF16_ROW_REL_L2):
     assert np.all(np.isfinite(got)), tag
     max_abs, rel = errors(got, ref)
-    print("%s: max_abs=%.3e rel_l2=%.3e" % (tag, max_abs, rel), flush=True)
+    worst, where = worst_row(got, ref)
+    print("%s: max_abs=%.3e rel_l2=%.3e row=%.3e" % (tag, max_abs, rel, worst), flush=True)
     assert max_abs <= BF16_MAX_ABS and rel <= BF16_REL_L2, (tag, max_abs, rel)
     assert rel <= BF16_REL_L2_INTERNAL, (tag, rel)
+    assert worst <= row_bound, (tag, worst, where)
 
 
 # ---- config c1: tiny fp32 -------------------------------------------------------------------
@@ -194,20 +195,26 @@ def test_future_frames_do_not_influence_past_rows_bitwise(attn_bf16):
     assert not np.array_equal(base[:, :, 4 * T:], pert[:, :, 4 * T:])
 
 
-# ---- the paper-shaped configs at full size, on sampled rows -------------------------------------
+# ---- the paper-shaped configs at full size --------------------------------------------------------
+# Every element of every output, in the launch configuration the benchmark times.  Only the long training form is
+# row-sampled (its oracle would take minutes): first and last row of each of its 64 frames + 64 random rows per frame.
 FULL = ["c2_train", "c3_decode", "c4_spec_k2", "c4_spec_k4", "c4_spec_k8", "c5a_long_train", "c5b_batch_decode",
         "x_train_h12", "x_train_h24", "x_decode_h12", "x_decode_h24", "x_spec_k3"]  # x_: other model sizes, N = 3
+SAMPLED = {"c5a_long_train": 64}
 
 
 @pytest.mark.parametrize("name", FULL)
-def test_full_size_configs_sampled_rows(attn_bf16, name):
+def test_full_size_configs(attn_bf16, name):
     cfg, q, k, v = wl.make_config(name)
     T, kvf, qf = cfg["T"], cfg["kv_frames"], cfg["q_frames"]
-    per_frame = {"c2_train": 8, "c5a_long_train": 3, "c5b_batch_decode": 24, "x_train_h12": 8, "x_train_h24": 8}.get(name, 32)
-    rows = wl.sample_rows(T, qf, per_frame, cfg["seed"])
     got = run_hip(attn_bf16, q, k, v, T, kvf, qf, "bf16")
-    ref = orc.block_causal_attn(q, k, v, T, kv_frames=kvf, q_frames=qf, rows=rows)
-    check_bf16(got[:, :, rows], ref, name + " (%d sampled rows/head)" % len(rows))
+    if name in SAMPLED:
+        rows = wl.sample_rows(T, qf, SAMPLED[name], cfg["seed"])
+        ref = orc.block_causal_attn(q, k, v, T, kv_frames=kvf, q_frames=qf, rows=rows)
+        check_bf16(got[:, :, rows], ref, name + " (%d sampled rows/head)" % len(rows))
+    else:
+        ref = orc.block_causal_attn(q, k, v, T, kv_frames=kvf, q_frames=qf)
+        check_bf16(got, ref, name + " (every element)")
     # convexity holds at any size: every output lies inside the range of V (bf16 rounding slack)
     assert np.abs(got).max() <= np.abs(v[:, :, : kvf * T]).max() * 1.01
 

@@ -4,6 +4,7 @@ ragged key blocks, frames that straddle tiles, head counts that do not divide by
 XCDs, spare cache capacity and key splits."""
 import numpy as np
 import pytest
+from parity_bounds import BF16_ROW_REL_L2, worst_row
 import torch
 
 from oracle import nfd_oracle as orc
@@ -69,6 +70,7 @@ def test_forward_and_backward_on_random_shapes(attn, B, H, T, kvf, qf, F):
         assert rel <= 5e-3 and np.abs(d).max() <= 2e-2 * max(1.0, np.abs(want).max()), (tag, rel, np.abs(d).max())
 
     close(_host(out), ref, "out")
+    assert worst_row(_host(out), ref)[0] <= BF16_ROW_REL_L2
     close(_host(dq), rdq, "dq")
     close(_host(dk)[:, :, :Sk], rdk[:, :, :Sk], "dk")
     close(_host(dv)[:, :, :Sk], rdv[:, :, :Sk], "dv")
@@ -133,7 +135,11 @@ def test_forward_many_heads_both_caches(attn, B, H, T, kvf, qf, F):
         assert rel <= 5e-3 and np.abs(d).max() <= 2e-2, (tag, rel, np.abs(d).max())
 
     kz, vz = np.nan_to_num(k), np.nan_to_num(v)
-    close(_host(out), orc.block_causal_attn(q, kz, vz, T, kv_frames=kvf, q_frames=qf), "bf16 cache")
+    ref16 = orc.block_causal_attn(q, kz, vz, T, kv_frames=kvf, q_frames=qf)
+    close(_host(out), ref16, "bf16 cache")
+    assert worst_row(_host(out), ref16)[0] <= BF16_ROW_REL_L2
     kq = f8.e4m3_decode(f8.quantize(kz[:, :, :Sk], ks[:, :, None, None])) * ks[:, :, None, None].astype(np.float64)
     vq = f8.e4m3_decode(f8.quantize(vz[:, :, :Sk], vs[:, :, None, None])) * vs[:, :, None, None].astype(np.float64)
-    close(_host(out8), orc.block_causal_attn(q, kq, vq, T, kv_frames=kvf, q_frames=qf), "8-bit cache")
+    ref8 = orc.block_causal_attn(q, kq, vq, T, kv_frames=kvf, q_frames=qf)
+    close(_host(out8), ref8, "8-bit cache")
+    assert worst_row(_host(out8), ref8)[0] <= BF16_ROW_REL_L2

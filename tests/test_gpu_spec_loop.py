@@ -4,6 +4,7 @@ cache write, attention, accept/reject, rollback - with every kept frame's attent
 checked against the fp64 oracle run on a host copy of the same cache."""
 import numpy as np
 import pytest
+from parity_bounds import BF16_ROW_REL_L2, worst_row
 import torch
 
 from oracle import nfd_oracle as orc
@@ -103,6 +104,7 @@ def test_speculative_decode_loop_with_window_and_rollback():
         ref = orc.block_causal_attn(_host(qr), hk, hv, T, kv_frames=st.kv_frames, q_frames=st.q_frames)
         d = _host(out) - ref
         assert np.abs(d).max() <= 2e-2 and np.linalg.norm(d) / np.linalg.norm(ref) <= 5e-3
+        assert worst_row(_host(out), ref)[0] <= BF16_ROW_REL_L2
         kept = nb.nfd_spec_accept(s, st, actions)
         assert kept == ex["kept"]
         # absolute temporal positions: cache slot 0 holds frame t_offset

@@ -2,7 +2,8 @@
 loop in oracle/spec_driver.py (Sec. 4.2; Appendix A), and pins of that statement by what the
 paper's description fixes: constant actions keep every chunk whole, ever-changing actions keep
 one frame per call, kept frames are exactly the leading run of the current action, every frame
-is produced once, the context never exceeds the window."""
+is produced once, the context never exceeds the window.  The window eviction as an array operation
+(kvcache_shift) is pinned by a cache whose every element encodes its own (frame, token, feature)."""
 import numpy as np
 import pytest
 
@@ -63,6 +64,59 @@ def test_context_never_exceeds_the_window_and_is_contiguous():
     for s in sd.run(a, n_prompt=3, nframe=4, window=8, capacity=12):
         c = s["cache_frames"]
         assert len(c) <= 8 and c == list(range(c[0], c[0] + len(c))) and c[-1] + 1 == s["generated"][0]
+
+
+def test_valid_prefix_hand_worked():
+    col = lambda *a: np.array(a, dtype=np.int32)[:, None]
+    assert sd.valid_prefix(col(3)) == 1                       # a chunk of one frame is always kept
+    assert sd.valid_prefix(col(3, 3, 3, 3)) == 4
+    assert sd.valid_prefix(col(3, 4, 3, 3)) == 1              # a later return to the action does not rescue frames
+    assert sd.valid_prefix(col(3, 3, 4, 3)) == 2
+    # multi-component actions differ if any component differs
+    assert sd.valid_prefix(np.array([[1, 2], [1, 2], [1, 3], [1, 2]], dtype=np.int32)) == 2
+    assert sd.valid_prefix(np.array([[1, 2], [0, 2]], dtype=np.int32)) == 1
+
+
+# ---- the window eviction as an array operation (Sec. 5 Limitations: fixed context window) ----------
+def _labelled_cache(B, H, F, T, D):
+    """cache[b, h, f*T + t, d] = a number from which (b, h, f, t, d) can be read back."""
+    b, h, f, t, d = np.meshgrid(np.arange(B), np.arange(H), np.arange(F), np.arange(T), np.arange(D), indexing="ij")
+    lab = ((((b * 7 + h) * 100 + f) * 100 + t) * 100 + d).astype(np.float64)
+    return lab.reshape(B, H, F * T, D)
+
+
+@pytest.mark.parametrize("B,H,F,T,D,kv,drop", [
+    (1, 1, 5, 3, 2, 5, 2),    # full cache
+    (2, 3, 9, 5, 7, 6, 1),    # odd sizes, spare capacity behind the cached frames
+    (1, 2, 8, 1, 3, 7, 5),    # one token per frame; more dropped than kept
+    (2, 1, 6, 4, 1, 4, 0),    # nothing dropped
+    (1, 2, 6, 4, 3, 4, 4),    # everything dropped
+    (1, 1, 4, 2, 2, 0, 0),    # empty cache
+])
+def test_kvcache_shift_against_labelled_frames(B, H, F, T, D, kv, drop):
+    cache = _labelled_cache(B, H, F, T, D)
+    before = cache.copy()
+    out = sd.kvcache_shift(cache, T, kv, drop)
+    assert np.array_equal(cache, before)                      # the input is not modified
+    assert out.shape == cache.shape
+    keep = kv - drop
+    for b in range(B):
+        for h in range(H):
+            for f in range(F):
+                src = f + drop if f < keep else f              # kept frames move down; the rest stays
+                for t in range(T):
+                    for d in range(D):
+                        want = (((b * 7 + h) * 100 + src) * 100 + t) * 100 + d
+                        assert out[b, h, f * T + t, d] == want, (b, h, f, t, d)
+
+
+def test_kvcache_shift_composes():
+    """Dropping a then b frames equals dropping a + b at once on the frames that remain."""
+    cache = _labelled_cache(1, 2, 10, 3, 2)
+    one = sd.kvcache_shift(sd.kvcache_shift(cache, 3, 9, 2), 3, 7, 3)
+    both = sd.kvcache_shift(cache, 3, 9, 5)
+    assert np.array_equal(one[:, :, : 4 * 3], both[:, :, : 4 * 3])
+    assert np.array_equal(both[:, :, 9 * 3:], cache[:, :, 9 * 3:])
 
 
 # ---- the library's bookkeeping against the statement -----------------------------------------------
