@@ -31,9 +31,6 @@ def main():
                     help="cached forms (decode, speculative): number of distinct K/V caches the steps rotate over")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of the oracle sample")
     ap.add_argument("--all", action="store_true", help="also time the other workloads (reported on stderr)")
-    ap.add_argument("--ceiling", action="store_true",
-                    help="also run the issue-mix probe: what the chip sustains for the kernel's MFMA : vector instruction "
-                         "mix with no memory traffic (stderr and 'issue_mix_ceiling')")
     ap.add_argument("--bwd", action="store_true",
                     help="also time the training step of the attention: forward with log-sum-exp + backward (stderr and 'backward')")
     ap.add_argument("--rope", action="store_true",
@@ -217,37 +214,6 @@ def main():
                     bwd_frac_mfma_peak=round(2.5 * fl / ms_b * 1e-9 / PEAK_BF16_TFLOPS, 4),
                     fwd_bwd_tflops=round(3.5 * fl / (ms_f + ms_b) * 1e-9, 2))
 
-    ceiling = None
-    if args.ceiling:
-        import ctypes
-        from paper_2506_01380_amd import build as nbuild
-        if not os.path.exists(nbuild.PROBE_LIB):
-            raise SystemExit("bench.py --ceiling: %s is missing (python -m paper_2506_01380_amd.build)" % nbuild.PROBE_LIB)
-        P = ctypes.CDLL(nbuild.PROBE_LIB)
-        P.nfd_probe_issue_mix.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
-                                          ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_double)]
-        cus = torch.cuda.get_device_properties(0).multi_processor_count
-        iters = 60000  # 35-80 ms per mode: long enough for the clock to settle under the power limit
-        ceiling = {"workgroups": cus, "iters": iters, "modes": {}}
-        # the last two modes launch two workgroups per CU: two wavefronts per SIMD, as in the attention kernel
-        for mode, gauss, wpc, nm in ((0, 0, 1, "mfma_only_narrow_operands"), (0, 1, 1, "mfma_only"), (1, 1, 1, "vector_only"),
-                                     (2, 1, 1, "sequential"), (3, 1, 1, "interleaved_1_to_7"),
-                                     (3, 0, 1, "interleaved_narrow_operands"), (2, 1, 2, "sequential_two_per_simd"),
-                                     (3, 1, 2, "interleaved_two_per_simd")):
-            ms, cyc = ctypes.c_float(0), ctypes.c_double(0)
-            n_it = iters // wpc
-            rc = P.nfd_probe_issue_mix(mode, cus * wpc, n_it, gauss, ctypes.byref(ms), ctypes.byref(cyc))
-            if rc != 0:
-                raise SystemExit("issue-mix probe failed with code %d" % rc)
-            # per iteration and wavefront: 32 MFMA of 32x32x16 = 1.049 MFLOP (not in the vector-only mode)
-            fl = 0.0 if mode == 1 else 32 * 2 * 32 * 32 * 16 * 4.0 * cus * wpc * n_it
-            # cycles per wave-tile and the clock they imply are given for one wavefront per SIMD only: with two, the
-            # counter of one wavefront no longer measures the SIMD's time per tile
-            ceiling["modes"][nm] = {"cycles_per_tile": round(cyc.value, 1) if wpc == 1 else None, "ms": round(ms.value, 4),
-                                    "mhz": round(cyc.value * n_it / (ms.value * 1e3), 0) if wpc == 1 else None,
-                                    "tflops": round(fl / ms.value * 1e-9, 1)}
-        print(json.dumps({"issue_mix_ceiling": ceiling}), file=sys.stderr, flush=True)
-
     backward = None
     if args.bwd:
         backward = time_bwd(args.workload, max(10, args.steps // 2), args.warmup)
@@ -352,8 +318,6 @@ def main():
                      "kernel": "attn_fwd_bf16_d64"},
         "cpu_baseline": cpu,
     }
-    if ceiling:
-        line["issue_mix_ceiling"] = ceiling
     if backward:
         line["backward"] = backward
     if pre_op:

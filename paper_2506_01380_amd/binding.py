@@ -296,42 +296,73 @@ class Attention:
         self.dtype = {"bf16": NFD_BF16, "fp32": NFD_FP32}[dtype]
         self.h = nfd_attn_create(self.dtype, device, workspace_bytes)
 
-    def forward(self, q, k, v, T, kv_frames=None, q_frames=None, out=None, scale=0.0, stream=None):
+    def _want(self):
         import torch
+        return torch.bfloat16 if self.dtype == NFD_BF16 else torch.float32
+
+    def _tensors(self, *ts):
+        """Every tensor handed to the library: on the GPU, dense, of the handle's dtype."""
+        want = self._want()
+        for t in ts:
+            if t.dtype != want or not t.is_contiguous() or not t.is_cuda or t.dim() != 4:
+                raise ValueError("tensors must be contiguous 4-D CUDA tensors of the handle's dtype")
+
+    def _geometry(self, q, k, v, T, kv_frames, q_frames):
+        """Checks q [B,H,q_frames*T,D] against k, v [B,H,F*T,D]; returns (B, H, F, D, kv_frames, q_frames)."""
+        self._tensors(q, k, v)
         B, H, Sq, D = q.shape
+        if T < 1 or Sq % T or k.shape[2] % T:
+            raise ValueError("sequence lengths must be multiples of T")
         F = k.shape[2] // T
         q_frames = Sq // T if q_frames is None else q_frames
         kv_frames = F if kv_frames is None else kv_frames
-        want = torch.bfloat16 if self.dtype == NFD_BF16 else torch.float32
-        for t in (q, k, v):
-            if t.dtype != want or not t.is_contiguous() or not t.is_cuda:
-                raise ValueError("tensors must be contiguous CUDA tensors of the handle's dtype")
-        if Sq != q_frames * T or k.shape != v.shape or k.shape[2] != F * T or k.shape[:2] != (B, H) or k.shape[3] != D:
-            raise ValueError("shape mismatch")
+        if Sq != q_frames * T or k.shape != v.shape or tuple(k.shape[:2]) != (B, H) or k.shape[3] != D:
+            raise ValueError("shape mismatch between q and k, v")
+        return B, H, F, D, kv_frames, q_frames
+
+    def _new_frames(self, k_cache, v_cache, k_new, v_new, T, *like_new):
+        """Checks the caches [B,H,F*T,D] against the new frames [B,H,n*T,D]; returns (B, H, F, D, n_frames)."""
+        self._tensors(k_cache, v_cache, k_new, v_new, *like_new)
+        B, H, Sc, D = k_cache.shape
+        if T < 1 or Sc % T or k_new.shape[2] % T:
+            raise ValueError("sequence lengths must be multiples of T")
+        if v_cache.shape != k_cache.shape or v_new.shape != k_new.shape or tuple(k_new.shape[:2]) != (B, H) or k_new.shape[3] != D:
+            raise ValueError("shape mismatch between the caches and the new frames")
+        for t in like_new:
+            if t.shape != k_new.shape:
+                raise ValueError("shape mismatch between q and the new frames")
+        return B, H, Sc // T, D, k_new.shape[2] // T
+
+    def forward(self, q, k, v, T, kv_frames=None, q_frames=None, out=None, scale=0.0, stream=None):
+        import torch
+        B, H, F, D, kv_frames, q_frames = self._geometry(q, k, v, T, kv_frames, q_frames)
         if out is None:
             out = torch.empty_like(q)
+        else:
+            self._tensors(out)
+            if out.shape != q.shape:
+                raise ValueError("out must have the shape of q")
         nfd_block_causal_attn_fwd(self.h, q, k, v, out, B, H, F, T, D, kv_frames, q_frames, scale, stream)
         return out
 
     def forward_lse(self, q, k, v, T, kv_frames=None, q_frames=None, scale=0.0, stream=None):
         """Forward that also returns the per-row log-sum-exp (fp32) for the backward call."""
         import torch
-        B, H, Sq, D = q.shape
-        F = k.shape[2] // T
-        kv_frames = F if kv_frames is None else kv_frames
-        q_frames = Sq // T if q_frames is None else q_frames
+        B, H, F, D, kv_frames, q_frames = self._geometry(q, k, v, T, kv_frames, q_frames)
         out = torch.empty_like(q)
-        lse = torch.empty((B, H, Sq), dtype=torch.float32, device=q.device)
+        lse = torch.empty((B, H, q.shape[2]), dtype=torch.float32, device=q.device)
         nfd_block_causal_attn_fwd_lse(self.h, q, k, v, out, lse, B, H, F, T, D, kv_frames, q_frames, scale, stream)
         return out, lse
 
     def backward(self, q, k, v, out, dout, lse, T, kv_frames=None, q_frames=None, scale=0.0, stream=None):
         """Gradients (dq, dk, dv); dk, dv have the shape of k, v (rows past kv_frames*T are zero)."""
         import torch
-        B, H, Sq, D = q.shape
-        F = k.shape[2] // T
-        kv_frames = F if kv_frames is None else kv_frames
-        q_frames = Sq // T if q_frames is None else q_frames
+        B, H, F, D, kv_frames, q_frames = self._geometry(q, k, v, T, kv_frames, q_frames)
+        self._tensors(out, dout)
+        if out.shape != q.shape or dout.shape != q.shape:
+            raise ValueError("out and dout must have the shape of q")
+        if lse.dtype != torch.float32 or not lse.is_cuda or not lse.is_contiguous() or tuple(lse.shape) != (B, H, q.shape[2]):
+            raise ValueError("lse must be a contiguous fp32 CUDA tensor [B, H, q_frames*T]")
         dq = torch.empty_like(q)
         dk, dv = torch.zeros_like(k), torch.zeros_like(v)
         nfd_block_causal_attn_bwd(self.h, q, k, v, out, dout, lse, dq, dk, dv, B, H, F, T, D, kv_frames, q_frames,
@@ -339,20 +370,22 @@ class Attention:
         return dq, dk, dv
 
     def append(self, k_cache, v_cache, k_new, v_new, T, frame_pos, stream=None):
-        B, H, Sc, D = k_cache.shape
-        n_frames = k_new.shape[2] // T
-        nfd_kvcache_append(self.h, k_cache, v_cache, k_new, v_new, B, H, Sc // T, T, D, frame_pos, n_frames, stream)
+        B, H, F, D, n_frames = self._new_frames(k_cache, v_cache, k_new, v_new, T)
+        nfd_kvcache_append(self.h, k_cache, v_cache, k_new, v_new, B, H, F, T, D, frame_pos, n_frames, stream)
 
     def rope_append(self, q, k_cache, v_cache, k_new, v_new, T, frame_pos, grid, sections, theta=0.0,
                     t_offset=0, q_out=None, stream=None):
         """Rotate q and k_new (3D rotary embedding), write rotated keys and values into the caches.
         Returns the rotated queries (q itself when q_out is q)."""
         import torch
-        B, H, Sc, D = k_cache.shape
-        n_frames = k_new.shape[2] // T
+        B, H, F, D, n_frames = self._new_frames(k_cache, v_cache, k_new, v_new, T, q)
         if q_out is None:
             q_out = torch.empty_like(q)
-        nfd_rope_kvcache_append(self.h, q, q_out, k_cache, v_cache, k_new, v_new, B, H, Sc // T, T, D, frame_pos,
+        else:
+            self._tensors(q_out)
+            if q_out.shape != q.shape:
+                raise ValueError("q_out must have the shape of q")
+        nfd_rope_kvcache_append(self.h, q, q_out, k_cache, v_cache, k_new, v_new, B, H, F, T, D, frame_pos,
                                 n_frames, t_offset, grid[0], grid[1], sections[0], sections[1], sections[2], theta,
                                 stream)
         return q_out

@@ -8,7 +8,6 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libnfd_attn.so")
-PROBE_LIB = os.path.join(HERE, "libnfd_probe.so")  # measurement aid (issue-mix ceiling), not part of the path
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 FLAGS = [
@@ -39,21 +38,6 @@ def build_library(verbose: bool = True, extra=()) -> str:
     return LIB
 
 
-def build_probe(verbose: bool = True) -> str:
-    """Compile the issue-mix probe (csrc/probe) into its own shared object."""
-    src = os.path.join(CSRC, "probe", "issue_mix_probe.hip")
-    tmp = PROBE_LIB + ".tmp%d" % os.getpid()
-    cmd = [HIPCC] + FLAGS + ["-o", tmp, src]
-    if verbose:
-        print(" ".join(cmd), flush=True)
-    res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
-    if res.returncode != 0:
-        raise RuntimeError("hipcc failed:\n" + res.stdout)
-    os.replace(tmp, PROBE_LIB)
-    return PROBE_LIB
-
-
 if __name__ == "__main__":
     build_library()
-    build_probe()
     sys.exit(0)

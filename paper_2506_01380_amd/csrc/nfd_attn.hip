@@ -10,6 +10,8 @@
 #include <cmath>
 #include <cstdio>
 #include <cstdlib>
+#include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 
@@ -23,7 +25,8 @@ struct nfd_attn {
     int num_cus;
     void* workspace;
     size_t workspace_bytes;
-    std::string err;
+    size_t plan_limit;  // workspace size the schedule is planned against (== workspace_bytes for created handles)
+    char err[256];      // fixed buffer: recording an error never allocates
 };
 
 namespace {
@@ -33,8 +36,21 @@ constexpr size_t kDefaultWorkspace = (size_t)128 << 20;
 constexpr size_t kPartialRowBytes = nfd::mfma::kD * 2 + 2 * sizeof(float);
 
 int fail(nfd_attn_t* h, int code, const std::string& msg) {
-    if (h) h->err = msg;
+    if (h) {
+        std::strncpy(h->err, msg.c_str(), sizeof(h->err) - 1);
+        h->err[sizeof(h->err) - 1] = 0;
+    }
     return code;
+}
+
+// Launches go to the device that is current on the calling thread; pointers and workspace belong to the
+// handle's device.  A mismatch would launch on the wrong device, so it is refused.
+int check_device(nfd_attn_t* h) {
+    int cur = -1;
+    const hipError_t e = hipGetDevice(&cur);
+    if (e != hipSuccess) return fail(h, NFD_ERR_HIP, std::string("hipGetDevice: ") + hipGetErrorString(e));
+    if (cur != h->device) return fail(h, NFD_ERR_UNSUPPORTED, "the current device is not the handle's device");
+    return NFD_OK;
 }
 
 int check_hip(nfd_attn_t* h, hipError_t e, const char* what) {
@@ -106,12 +122,6 @@ int nfd_attn_plan(nfd_dtype_t dtype, int B, int H, int F, int T, int D, int kv_f
             tile_counts(nfd::mfma::kBM / 2);
             wg_per_cu = 3;
         }
-#ifdef NFD_TUNE_SPLITS  // development build: force the workgroup shape from the environment
-        if (const char* e = getenv("NFD_BM")) {
-            tile_counts(atoi(e) == 128 ? 128 : 256);
-            wg_per_cu = atoi(e) == 128 ? 3 : 2;
-        }
-#endif
         // Key splits: only when the query tiles alone cannot fill the chip (cached forms).  The count
         // minimises a small cost model in units of the time one workgroup needs for one key tile when
         // two workgroups share a CU: workgroups run in rounds of 2 per CU; a workgroup that has its CU
@@ -134,13 +144,6 @@ int nfd_attn_plan(nfd_dtype_t dtype, int B, int H, int F, int T, int D, int kv_f
                 if (cost < best) { best = cost; splits = s; }
             }
         }
-#ifdef NFD_TUNE_SPLITS  // development build: sweep the split count from the environment
-        if (const char* e = getenv("NFD_SPLITS")) {
-            const size_t per_split = (size_t)(BH * Sq) * kPartialRowBytes;
-            splits = std::max(1, std::min(atoi(e), (int)std::max<int64_t>(1, max_tiles / 2)));
-            while (splits > 1 && per_split * splits > workspace_limit) --splits;  // never beyond the workspace
-        }
-#endif
         pl.n_splits = splits;
         if (BH * pl.n_q_tiles * splits > (int64_t)0x7fffffff) return NFD_ERR_UNSUPPORTED;  // grid size
         pl.n_workgroups = (int)(BH * pl.n_q_tiles * splits);
@@ -185,6 +188,8 @@ int nfd_attn_create(nfd_attn_t** out, nfd_dtype_t dtype, int device, size_t work
     h->device = device;
     h->workspace = nullptr;
     h->workspace_bytes = workspace_bytes ? workspace_bytes : kDefaultWorkspace;
+    h->plan_limit = h->workspace_bytes;
+    h->err[0] = 0;
     int prev = 0;
     hipError_t e = hipGetDevice(&prev);
     if (e == hipSuccess) e = hipSetDevice(device);
@@ -219,7 +224,7 @@ int nfd_attn_destroy(nfd_attn_t* h) {
     return e == hipSuccess ? NFD_OK : NFD_ERR_HIP;
 }
 
-const char* nfd_last_error(const nfd_attn_t* h) { return h ? h->err.c_str() : "null handle"; }
+const char* nfd_last_error(const nfd_attn_t* h) { return h ? h->err : "null handle"; }
 
 // k_scale / v_scale non-null: k and v are the 8-bit caches (see nfd_kvcache_append_fp8).
 static int fwd_impl(nfd_attn_t* h, const void* q, const void* k, const void* v, void* out, float* lse, int B,
@@ -229,11 +234,13 @@ static int fwd_impl(nfd_attn_t* h, const void* q, const void* k, const void* v, 
     if (!q || !k || !v || !out) return fail(h, NFD_ERR_NULL, "q, k, v and out must be non-null");
     const bool kv8 = k_scale != nullptr;
     nfd_attn_plan_t pl;
-    const int rc = nfd_attn_plan(h->dtype, B, H, F, T, D, kv_frames, q_frames, h->num_cus, h->workspace_bytes, &pl);
+    const int rc = nfd_attn_plan(h->dtype, B, H, F, T, D, kv_frames, q_frames, h->num_cus, h->plan_limit, &pl);
     if (rc != NFD_OK) return fail(h, rc, "invalid shape arguments");
-    // The plan is made against this handle's workspace; a schedule that would write partials past it
-    // must never reach the device.
-    if (pl.workspace_bytes > h->workspace_bytes) return fail(h, NFD_ERR_ALLOC, "key-split partials exceed the workspace");
+    // A schedule that would write partials past the workspace must never reach the device.
+    if (pl.workspace_bytes > h->workspace_bytes)
+        return fail(h, NFD_ERR_ALLOC, "key-split partials (" + std::to_string(pl.workspace_bytes) + " bytes) exceed the scratch memory (" +
+                                          std::to_string(h->workspace_bytes) + " bytes)");
+    if (const int dc = check_device(h)) return dc;
     // The matrix-core kernels move 16-byte vectors; a view that starts in the middle of a vector would fault.
     if (pl.kernel == 1 && (((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)out) % 16 != 0 || (uintptr_t)lse % 4 != 0))
         return fail(h, NFD_ERR_UNSUPPORTED, "q, k, v, out must be 16-byte aligned (lse 4-byte)");
@@ -335,6 +342,7 @@ int nfd_kvcache_append_fp8(nfd_attn_t* h, void* k8, void* v8t, const float* k_sc
         ((uintptr_t)k_scale | (uintptr_t)v_scale) % 4 != 0)
         return fail(h, NFD_ERR_UNSUPPORTED, "caches and new tensors must be 16-byte aligned (scales 4-byte)");
     if (n_frames == 0) return NFD_OK;
+    if (const int dc = check_device(h)) return dc;
     const int n_rows = n_frames * T, j0 = frame_pos * T, BH = B * H;
     const int64_t Spad = ((int64_t)F * T + 63) / 64 * 64;
     hipStream_t st = (hipStream_t)stream;
@@ -356,6 +364,7 @@ int nfd_block_causal_attn_bwd(nfd_attn_t* h, const void* q, const void* k, const
     if (rc != NFD_OK) return fail(h, rc, "invalid shape arguments");
     const int64_t BH = (int64_t)B * H, Sq = (int64_t)q_frames * T, Sk = (int64_t)kv_frames * T;
     if (h->dtype != NFD_BF16 || D != nfd::mfma::kD) {
+        if (const int dc = check_device(h)) return dc;
         // general path: fp32 arithmetic, one wavefront per row
         if ((size_t)(BH * Sq) * sizeof(float) > h->workspace_bytes)
             return fail(h, NFD_ERR_ALLOC, "the per-row workspace of the backward exceeds the handle's workspace");
@@ -399,6 +408,9 @@ int nfd_block_causal_attn_bwd(nfd_attn_t* h, const void* q, const void* k, const
     p.n_k_blocks = (int)((Sk + 4 * kKeysPerWave - 1) / (4 * kKeysPerWave));
     p.scale = scale;
     p.scale_log2e = scale * nfd::kLog2e;
+    if (BH * p.n_q_tiles > (int64_t)0x7fffffff || BH * p.n_k_blocks > (int64_t)0x7fffffff)
+        return fail(h, NFD_ERR_UNSUPPORTED, "too many workgroups for one launch of the backward");
+    if (const int dc = check_device(h)) return dc;
     hipStream_t st = (hipStream_t)stream;
     const unsigned heads8 = (unsigned)BH;  // one workgroup per (head, item)
     // the dq kernel first: it writes the per-row delta that the dk/dv kernel reads
@@ -471,6 +483,7 @@ int nfd_kvcache_append(nfd_attn_t* h, void* k_cache, void* v_cache, const void* 
         return fail(h, NFD_ERR_SHAPE, "invalid shape arguments");
     if ((int64_t)frame_pos + n_frames > F) return fail(h, NFD_ERR_CAPACITY, "frame_pos + n_frames exceeds the cache capacity F");
     if (n_frames == 0) return NFD_OK;
+    if (const int dc = check_device(h)) return dc;
     const int64_t frame_elems = (int64_t)T * D;
     launch_frame_copy(h, elem_size(h->dtype), k_cache, v_cache, k_new, v_new, (int64_t)B * H, (int64_t)F * frame_elems,
                       (int64_t)n_frames * frame_elems, (int64_t)frame_pos * frame_elems, 0,
@@ -486,6 +499,7 @@ int nfd_kvcache_shift(nfd_attn_t* h, void* k_cache, void* v_cache, int B, int H,
         return fail(h, NFD_ERR_SHAPE, "invalid shape arguments");
     if (kv_frames > F) return fail(h, NFD_ERR_CAPACITY, "kv_frames exceeds the cache capacity F");
     if (n_drop == 0 || kv_frames == n_drop) return NFD_OK;
+    if (const int dc = check_device(h)) return dc;
     shift_frames(h, elem_size(h->dtype), k_cache, v_cache, (int64_t)B * H, (int64_t)F * T * D, (int64_t)T * D, kv_frames,
                  n_drop, (hipStream_t)stream);
     return check_hip(h, hipGetLastError(), "kvcache shift launch");
@@ -506,6 +520,7 @@ int nfd_kvcache_shift_fp8(nfd_attn_t* h, void* k8, void* v8t, int B, int H, int 
     const int64_t keep_keys = (int64_t)(kv_frames - n_drop) * T;
     if (T % 16 != 0 && h->workspace_bytes < (size_t)keep_keys)  // checked before anything is launched
         return fail(h, NFD_ERR_ALLOC, "the workspace cannot stage one feature row of the 8-bit V cache");
+    if (const int dc = check_device(h)) return dc;
     hipStream_t st = (hipStream_t)stream;
     // K codes: BH heads of Spad rows x 64 bytes, a frame = T rows; V codes: BH * 64 feature rows of Spad bytes,
     // a frame = T bytes of each.  (One tensor at a time: the geometries differ.)
@@ -603,6 +618,7 @@ static int rope_impl(nfd_attn_t* h, const void* q, void* q_out, void* k_cache, v
             return fail(h, NFD_ERR_UNSUPPORTED, "tensors must be 16-byte aligned (scales 4-byte)");
     }
     if (n_frames == 0) return NFD_OK;
+    if (const int dc = check_device(h)) return dc;
     const double th = theta > 0.f ? (double)theta : 10000.0;
     nfd::RopeTable tab{};
     {

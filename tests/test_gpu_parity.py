@@ -327,3 +327,42 @@ def test_runs_are_bit_reproducible(attn_bf16):
     a = run_hip(attn_bf16, q, k, v, cfg["T"], cfg["kv_frames"], cfg["q_frames"], "bf16")
     b = run_hip(attn_bf16, q, k, v, cfg["T"], cfg["kv_frames"], cfg["q_frames"], "bf16")
     assert np.array_equal(a, b)
+
+
+def test_wrapper_methods_validate_their_tensors(attn_bf16):
+    """A wrong dtype, a strided view, a host tensor or a length that is not a multiple of T must raise in the
+    binding instead of reaching the device as a wrong stride."""
+    B, H, T, D, F = 1, 2, 16, 64, 3
+    mk = lambda *s: torch.zeros(*s, dtype=torch.bfloat16, device="cuda")
+    q, k, v = mk(B, H, F * T, D), mk(B, H, F * T, D), mk(B, H, F * T, D)
+    out, lse = attn_bf16.forward_lse(q, k, v, T)
+    bad_sets = [
+        dict(k=k.float()),                                       # dtype of the handle
+        dict(k=mk(B, H, F * T, 2 * D)[..., ::2]),                # not contiguous
+        dict(v=v.cpu()),                                         # not on the device
+        dict(k=mk(B, H, F * T + 1, D), v=mk(B, H, F * T + 1, D)),  # cache length not a multiple of T
+        dict(v=mk(B, H, 2 * F * T, D)),                          # k and v disagree
+        dict(q=mk(B, H + 1, F * T, D)),                          # heads disagree
+    ]
+    for bad in bad_sets:
+        a = dict(q=q, k=k, v=v)
+        a.update(bad)
+        for call in (lambda: attn_bf16.forward(a["q"], a["k"], a["v"], T),
+                     lambda: attn_bf16.forward_lse(a["q"], a["k"], a["v"], T),
+                     lambda: attn_bf16.backward(a["q"], a["k"], a["v"], out, out, lse, T)):
+            with pytest.raises(ValueError):
+                call()
+    with pytest.raises(ValueError):
+        attn_bf16.backward(q, k, v, out, out, lse.double(), T)
+    kn = mk(B, H, T, D)
+    for bad in (dict(k_new=kn.float()), dict(k_new=mk(B, H, T + 1, D), v_new=mk(B, H, T + 1, D)), dict(v_cache=v.cpu()),
+                dict(k_new=mk(B, H + 1, T, D), v_new=mk(B, H + 1, T, D))):
+        a = dict(k_cache=k, v_cache=v, k_new=kn, v_new=kn)
+        a.update(bad)
+        with pytest.raises(ValueError):
+            attn_bf16.append(a["k_cache"], a["v_cache"], a["k_new"], a["v_new"], T, 0)
+        with pytest.raises(ValueError):
+            attn_bf16.rope_append(kn, a["k_cache"], a["v_cache"], a["k_new"], a["v_new"], T, 0, (4, 4), (16, 24, 24))
+    with pytest.raises(ValueError):
+        attn_bf16.rope_append(mk(B, H, 2 * T, D), k, v, kn, kn, T, 0, (4, 4), (16, 24, 24))  # q and the new frames disagree
+    torch.cuda.synchronize()
