@@ -83,6 +83,30 @@ int nfd_block_causal_attn_fwd(nfd_attn_t* h, const void* q, const void* k, const
                               float scale, void* stream);
 
 /*
+ * nfd_block_causal_attn_fwd for callers that cannot allocate device memory and therefore cannot create a
+ * handle: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  No handle;
+ * the key-split partials, which the handle version keeps in its workspace, go to a fixed array of
+ * NFD_NOALLOC_SCRATCH_BYTES inside the library's code object (each GPU the library runs on holds its own
+ * copy until the process ends).  The call makes no hipMalloc / hipFree and no host heap allocation.
+ *   dtype            : element type of q, k, v, out (as nfd_attn_create's)
+ *   q, k, v, out ... : exactly as for nfd_block_causal_attn_fwd; runs on the device current on the calling thread
+ *   err, err_len     : optional host buffer that receives the error text ("" on success); may be NULL / 0
+ * The schedule is the one a handle with the default workspace uses, so the output is bit-identical to
+ * nfd_block_causal_attn_fwd's.  A call whose partials would not fit the array (bf16, D = 64, key-split
+ * launches only: B*H*q_frames*T*splits*136 bytes) is refused with NFD_ERR_ALLOC before anything is launched;
+ * nothing is re-planned.  Calls that need no key split (training form, fp32, other head widths) use no scratch.
+ * The array keeps the previous call's partials; nothing in it has to start at zero (every partial row a
+ * launch reads, it has written before).  All calls on one GPU share the one array: calls that overlap in
+ * time on the same GPU (two streams, two threads) race; order them on one stream.
+ * The first call on a device looks up the array's device address and the device's properties: make it
+ * outside stream capture.  Other errors as for nfd_block_causal_attn_fwd.
+ */
+#define NFD_NOALLOC_SCRATCH_BYTES ((size_t)32 << 20)
+int nfd_block_causal_attn_fwd_noalloc(nfd_dtype_t dtype, const void* q, const void* k, const void* v, void* out, int B,
+                                      int H, int F, int T, int D, int kv_frames, int q_frames, float scale, void* stream,
+                                      char* err, size_t err_len);
+
+/*
  * The same forward, additionally writing lse[b,h,i] = log sum_{visible j} exp(scale <q_i, k_j>)
  * (fp32, [B, H, q_frames*T]), which the backward call below consumes.  Arguments, support and
  * errors as for nfd_block_causal_attn_fwd; lse == NULL is NFD_ERR_NULL.

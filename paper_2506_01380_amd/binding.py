@@ -27,6 +27,7 @@ EXPORTS = (
     "nfd_rope_kvcache_append", "nfd_rope_check_args",
     "nfd_block_causal_attn_fwd_lse", "nfd_block_causal_attn_bwd",
     "nfd_kvcache_shift", "nfd_spec_init", "nfd_spec_next", "nfd_spec_accept", "nfd_attn_work_item",
+    "nfd_block_causal_attn_fwd_noalloc",
     "nfd_fp8_cache_bytes", "nfd_kvcache_append_fp8", "nfd_block_causal_attn_fwd_fp8kv", "nfd_kvcache_shift_fp8", "nfd_rope_kvcache_append_fp8",
 )
 
@@ -78,6 +79,8 @@ def lib():
         L.nfd_attn_create.restype = ci
         L.nfd_block_causal_attn_fwd.argtypes = [vp, vp, vp, vp, vp] + [ci] * 7 + [cf, vp]
         L.nfd_block_causal_attn_fwd.restype = ci
+        L.nfd_block_causal_attn_fwd_noalloc.argtypes = [ci, vp, vp, vp, vp] + [ci] * 7 + [cf, vp, ctypes.c_char_p, ctypes.c_size_t]
+        L.nfd_block_causal_attn_fwd_noalloc.restype = ci
         L.nfd_block_causal_attn_fwd_lse.argtypes = [vp] * 6 + [ci] * 7 + [cf, vp]
         L.nfd_block_causal_attn_fwd_lse.restype = ci
         L.nfd_block_causal_attn_bwd.argtypes = [vp] * 10 + [ci] * 7 + [cf, vp]
@@ -158,6 +161,15 @@ def nfd_block_causal_attn_fwd(h, q, k, v, out, B, H, F, T, D, kv_frames, q_frame
     rc = lib().nfd_block_causal_attn_fwd(h, _addr(q), _addr(k), _addr(v), _addr(out), B, H, F, T, D,
                                          kv_frames, q_frames, scale, _stream(stream))
     _check(rc, "nfd_block_causal_attn_fwd", h)
+
+
+def nfd_block_causal_attn_fwd_noalloc(dtype, q, k, v, out, B, H, F, T, D, kv_frames, q_frames, scale=0.0, stream=None):
+    """The handle-free forward whose scratch is a fixed array inside the library (see the header)."""
+    err = ctypes.create_string_buffer(256)
+    rc = lib().nfd_block_causal_attn_fwd_noalloc(dtype, _addr(q), _addr(k), _addr(v), _addr(out), B, H, F, T, D,
+                                                 kv_frames, q_frames, scale, _stream(stream), err, len(err))
+    if rc != NFD_OK:
+        raise NfdError(rc, "nfd_block_causal_attn_fwd_noalloc", err.value.decode())
 
 
 def nfd_block_causal_attn_fwd_lse(h, q, k, v, out, lse, B, H, F, T, D, kv_frames, q_frames, scale=0.0, stream=None):

@@ -8,12 +8,12 @@
 
 #include <algorithm>
 #include <cmath>
+#include <cstdarg>
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
 #include <mutex>
 #include <new>
-#include <string>
 
 #include "kernels_generic.hpp"
 #include "kernels_mfma.hpp"
@@ -35,10 +35,13 @@ constexpr size_t kDefaultWorkspace = (size_t)128 << 20;
 // one row of one key split in the workspace: 64 bf16 partial outputs + (max, sum) in fp32
 constexpr size_t kPartialRowBytes = nfd::mfma::kD * 2 + 2 * sizeof(float);
 
-int fail(nfd_attn_t* h, int code, const std::string& msg) {
+// Record an error text in the handle's fixed buffer (printf-style; no allocation) and return the code.
+__attribute__((format(printf, 3, 4))) int fail(nfd_attn_t* h, int code, const char* fmt, ...) {
     if (h) {
-        std::strncpy(h->err, msg.c_str(), sizeof(h->err) - 1);
-        h->err[sizeof(h->err) - 1] = 0;
+        va_list ap;
+        va_start(ap, fmt);
+        std::vsnprintf(h->err, sizeof(h->err), fmt, ap);
+        va_end(ap);
     }
     return code;
 }
@@ -48,14 +51,14 @@ int fail(nfd_attn_t* h, int code, const std::string& msg) {
 int check_device(nfd_attn_t* h) {
     int cur = -1;
     const hipError_t e = hipGetDevice(&cur);
-    if (e != hipSuccess) return fail(h, NFD_ERR_HIP, std::string("hipGetDevice: ") + hipGetErrorString(e));
+    if (e != hipSuccess) return fail(h, NFD_ERR_HIP, "hipGetDevice: %s", hipGetErrorString(e));
     if (cur != h->device) return fail(h, NFD_ERR_UNSUPPORTED, "the current device is not the handle's device");
     return NFD_OK;
 }
 
 int check_hip(nfd_attn_t* h, hipError_t e, const char* what) {
     if (e == hipSuccess) return NFD_OK;
-    return fail(h, NFD_ERR_HIP, std::string(what) + ": " + hipGetErrorString(e));
+    return fail(h, NFD_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
 }
 
 size_t elem_size(nfd_dtype_t dt) { return dt == NFD_BF16 ? 2 : 4; }
@@ -200,8 +203,7 @@ int nfd_attn_create(nfd_attn_t** out, nfd_dtype_t dtype, int device, size_t work
         return NFD_ERR_HIP;
     }
     h->num_cus = prop.multiProcessorCount;
-    const std::string arch = prop.gcnArchName;
-    if (arch.rfind("gfx950", 0) != 0) {
+    if (std::strncmp(prop.gcnArchName, "gfx950", 6) != 0) {
         (void)hipSetDevice(prev);
         delete h;
         return NFD_ERR_UNSUPPORTED;  // the kernels are written for CDNA4 only
@@ -238,8 +240,8 @@ static int fwd_impl(nfd_attn_t* h, const void* q, const void* k, const void* v, 
     if (rc != NFD_OK) return fail(h, rc, "invalid shape arguments");
     // A schedule that would write partials past the workspace must never reach the device.
     if (pl.workspace_bytes > h->workspace_bytes)
-        return fail(h, NFD_ERR_ALLOC, "key-split partials (" + std::to_string(pl.workspace_bytes) + " bytes) exceed the scratch memory (" +
-                                          std::to_string(h->workspace_bytes) + " bytes)");
+        return fail(h, NFD_ERR_ALLOC, "key-split partials (%zu bytes) exceed the scratch memory (%zu bytes)", pl.workspace_bytes,
+                    h->workspace_bytes);
     if (const int dc = check_device(h)) return dc;
     // The matrix-core kernels move 16-byte vectors; a view that starts in the middle of a vector would fault.
     if (pl.kernel == 1 && (((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)out) % 16 != 0 || (uintptr_t)lse % 4 != 0))
@@ -296,6 +298,67 @@ int nfd_block_causal_attn_fwd(nfd_attn_t* h, const void* q, const void* k, const
                               int H, int F, int T, int D, int kv_frames, int q_frames, float scale,
                               void* stream) {
     return fwd_impl(h, q, k, v, out, nullptr, B, H, F, T, D, kv_frames, q_frames, scale, stream);
+}
+
+// ---- forward for callers that cannot allocate ---------------------------------------------------------
+// The key-split partials go to a fixed array in the code object instead of a handle's workspace.  `scratch`
+// is only a host-side stand-in for the symbol: the address the kernels get is the one hipGetSymbolAddress
+// returns with the device current, looked up once per device and kept in that device's pseudo-handle.
+namespace {
+constexpr size_t kStaticScratchBytes = NFD_NOALLOC_SCRATCH_BYTES;
+constexpr int kStaticMaxDevices = 64;
+struct StaticDevice {
+    bool ready;
+    void* scratch_ptr;  // device address of `scratch` on this device
+    int num_cus;
+};
+StaticDevice g_static_dev[kStaticMaxDevices];
+std::mutex g_static_mu;
+}  // namespace
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+int nfd_block_causal_attn_fwd_noalloc(nfd_dtype_t dtype, const void* q, const void* k, const void* v, void* out, int B,
+                                      int H, int F, int T, int D, int kv_frames, int q_frames, float scale, void* stream,
+                                      char* err, size_t err_len) {
+    nfd_attn local{};  // pseudo-handle on the stack: nothing is allocated, the error text lands in its buffer
+    auto done = [&](int rc) {
+        if (err && err_len) {
+            std::strncpy(err, rc == NFD_OK ? "" : local.err, err_len - 1);
+            err[err_len - 1] = 0;
+        }
+        return rc;
+    };
+    if (dtype != NFD_BF16 && dtype != NFD_FP32) return done(fail(&local, NFD_ERR_UNSUPPORTED, "unknown dtype"));
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return done(check_hip(&local, e, "hipGetDevice"));
+    if (dev < 0 || dev >= kStaticMaxDevices) return done(fail(&local, NFD_ERR_UNSUPPORTED, "device index beyond the table of this entry point"));
+    {
+        std::lock_guard<std::mutex> lock(g_static_mu);
+        StaticDevice& sd = g_static_dev[dev];
+        if (!sd.ready) {  // first call on this device, with it current: where this device keeps its copy of the array
+            void* ptr = nullptr;
+            e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+            if (e != hipSuccess || !ptr) return done(check_hip(&local, e == hipSuccess ? hipErrorInvalidSymbol : e, "hipGetSymbolAddress(scratch)"));
+            hipDeviceProp_t prop;
+            e = hipGetDeviceProperties(&prop, dev);
+            if (e != hipSuccess) return done(check_hip(&local, e, "hipGetDeviceProperties"));
+            if (std::strncmp(prop.gcnArchName, "gfx950", 6) != 0)
+                return done(fail(&local, NFD_ERR_UNSUPPORTED, "the kernels are written for gfx950 only"));
+            sd.scratch_ptr = ptr;
+            sd.num_cus = prop.multiProcessorCount;
+            sd.ready = true;
+        }
+        local.workspace = sd.scratch_ptr;  // never the array's name: that is not a device address
+        local.num_cus = sd.num_cus;
+    }
+    local.dtype = dtype;
+    local.device = dev;
+    local.workspace_bytes = kStaticScratchBytes;
+    // The schedule is the one a handle with the default workspace would get, so the result is bit-identical to
+    // nfd_block_causal_attn_fwd's; a call whose partials do not fit the array is refused (NFD_ERR_ALLOC), not re-planned.
+    local.plan_limit = kDefaultWorkspace;
+    return done(fwd_impl(&local, q, k, v, out, nullptr, B, H, F, T, D, kv_frames, q_frames, scale, stream));
 }
 
 int nfd_block_causal_attn_fwd_lse(nfd_attn_t* h, const void* q, const void* k, const void* v, void* out,

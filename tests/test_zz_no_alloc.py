@@ -1,0 +1,91 @@
+"""GPU: the allocation-free forward (fixed scratch array inside the library) against the handle version, through
+the C ABI: bit-identical outputs on two calls in a row, the second smaller than the first (so it finds the first
+call's partials in the array), within the bf16 bounds of the oracle, and a clear error beyond the array's size."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import nfd_oracle as orc
+from paper_2506_01380_amd import binding as nb
+from paper_2506_01380_amd import workloads as wl
+from parity_bounds import BF16_MAX_ABS, BF16_REL_L2_INTERNAL, BF16_ROW_REL_L2, worst_row
+
+pytestmark = pytest.mark.gpu
+
+
+def _dev(x):
+    return torch.from_numpy(x).cuda().to(torch.bfloat16)
+
+
+def _both(attn, q, k, v, B, H, F, T, D, kvf, qf):
+    qd, kd, vd = _dev(q), _dev(k), _dev(v)
+    want = torch.empty_like(qd)
+    nb.nfd_block_causal_attn_fwd(attn.h, qd, kd, vd, want, B, H, F, T, D, kvf, qf)
+    got = torch.full_like(qd, float("nan"))
+    nb.nfd_block_causal_attn_fwd_noalloc(nb.NFD_BF16, qd, kd, vd, got, B, H, F, T, D, kvf, qf)
+    torch.cuda.synchronize()
+    return got, want
+
+
+def test_noalloc_forward_equals_handle_forward_twice_in_a_row():
+    attn = nb.Attention("bf16")
+    # first call: the 4-frame speculative step (key splits: 14.6 MB of partials); second: a smaller 1-frame decode
+    # over a shorter cache (its partials overwrite only part of what the first call left in the array)
+    for name, shrink in (("c4_spec_k4", None), ("c3_decode", 20)):
+        cfg, q, k, v = wl.make_config(name)
+        B, H, D, T, kvf, qf, F = (cfg[x] for x in ("B", "H", "D", "T", "kv_frames", "q_frames", "F"))
+        if shrink:
+            kvf = shrink
+        plan = nb.nfd_attn_plan(nb.NFD_BF16, B, H, F, T, D, kvf, qf)
+        assert plan["n_splits"] > 1 and 0 < plan["workspace_bytes"] <= 32 << 20   # the scratch path is exercised
+        got, want = _both(attn, q, k, v, B, H, F, T, D, kvf, qf)
+        assert torch.equal(got, want), name
+        g = got.float().cpu().numpy().astype(np.float64)
+        ref = orc.block_causal_attn(q, k, v, T, kv_frames=kvf, q_frames=qf)
+        d = g - ref
+        assert np.abs(d).max() <= BF16_MAX_ABS and np.linalg.norm(d) / np.linalg.norm(ref) <= BF16_REL_L2_INTERNAL, name
+        assert worst_row(g, ref)[0] <= BF16_ROW_REL_L2, name
+    attn.close()
+
+
+def test_noalloc_forward_without_splits_and_fp32():
+    attn16, attn32 = nb.Attention("bf16"), nb.Attention("fp32")
+    B, H, T, D, F = 2, 8, 48, 64, 7   # training form: no key split, no scratch
+    q, k, v = wl.make_qkv(B, H, D, T, F, F, F, "bf16", seed=wl.BASE_SEED + 700)
+    got, want = _both(attn16, q, k, v, B, H, F, T, D, F, F)
+    assert torch.equal(got, want)
+    cfg, q, k, v = wl.make_config("c1_tiny_fp32")
+    qd, kd, vd = (torch.from_numpy(x).cuda() for x in (q, k, v))
+    want, got = torch.empty_like(qd), torch.empty_like(qd)
+    a = (cfg["B"], cfg["H"], cfg["F"], cfg["T"], cfg["D"], cfg["kv_frames"], cfg["q_frames"])
+    nb.nfd_block_causal_attn_fwd(attn32.h, qd, kd, vd, want, *a)
+    nb.nfd_block_causal_attn_fwd_noalloc(nb.NFD_FP32, qd, kd, vd, got, *a)
+    torch.cuda.synchronize()
+    assert torch.equal(got, want)
+    assert np.abs(got.cpu().numpy().astype(np.float64) - orc.block_causal_attn(q, k, v, cfg["T"])).max() <= 1e-4
+    attn16.close()
+    attn32.close()
+
+
+def test_noalloc_forward_refuses_what_does_not_fit_and_bad_arguments():
+    # the batched long-context decode needs 40 MB of partials: beyond the 32 MiB array -> refused, nothing launched
+    cfg = wl.CONFIGS["c5b_batch_decode"]
+    B, H, D, T, kvf, qf, F = (cfg[x] for x in ("B", "H", "D", "T", "kv_frames", "q_frames", "F"))
+    assert nb.nfd_attn_plan(nb.NFD_BF16, B, H, F, T, D, kvf, qf)["workspace_bytes"] > 32 << 20
+    q = torch.zeros((B, H, qf * T, D), dtype=torch.bfloat16, device="cuda")
+    k = torch.zeros((B, H, F * T, D), dtype=torch.bfloat16, device="cuda")
+    out = torch.full_like(q, 3.0)
+    with pytest.raises(nb.NfdError) as e:
+        nb.nfd_block_causal_attn_fwd_noalloc(nb.NFD_BF16, q, k, k, out, B, H, F, T, D, kvf, qf)
+    assert e.value.code == nb.NFD_ERR_ALLOC and "exceed the scratch memory" in str(e.value)
+    torch.cuda.synchronize()
+    assert bool((out == 3.0).all())
+    with pytest.raises(nb.NfdError) as e:
+        nb.nfd_block_causal_attn_fwd_noalloc(nb.NFD_BF16, q, k, None, out, B, H, F, T, D, kvf, qf)
+    assert e.value.code == nb.NFD_ERR_NULL
+    with pytest.raises(nb.NfdError) as e:
+        nb.nfd_block_causal_attn_fwd_noalloc(nb.NFD_BF16, q, k, k, out, B, H, F, T, D, F + 1, qf)
+    assert e.value.code == nb.NFD_ERR_CAPACITY
+    with pytest.raises(nb.NfdError) as e:
+        nb.nfd_block_causal_attn_fwd_noalloc(7, q, k, k, out, B, H, F, T, D, kvf, qf)
+    assert e.value.code == nb.NFD_ERR_UNSUPPORTED
