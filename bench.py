@@ -30,6 +30,11 @@ def main():
     ap.add_argument("--cache-sets", type=int, default=16,
                     help="cached forms (decode, speculative): number of distinct K/V caches the steps rotate over")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of the oracle sample")
+    ap.add_argument("--settle-ms", type=float, default=150.0,
+                    help="the warm-up runs its --warmup steps and then keeps stepping until this much GPU time has passed: "
+                         "from idle the chip boosts, overshoots its power limit, throttles and needs about 60 launches of the "
+                         "training form (20-30 ms) to settle; 0 = exactly --warmup steps")
+    ap.add_argument("--no-check", action="store_true", help="skip the comparison of the timed output with the oracle")
     ap.add_argument("--all", action="store_true", help="also time the other workloads (reported on stderr)")
     ap.add_argument("--bwd", action="store_true",
                     help="also time the training step of the attention: forward with log-sum-exp + backward (stderr and 'backward')")
@@ -55,6 +60,22 @@ def main():
         sys.exit(2)
     torch.cuda.set_device(0)
     attn = nb.Attention("bf16")
+
+    def oracle_check(tensors, cfg):
+        """The output the last timed step left behind against the fp64 oracle on the same device-drawn inputs, on
+        sampled query rows (first and last row of every query frame plus a few seeded random ones; all heads)."""
+        from oracle import nfd_oracle as orc
+        q, k, v, out = tensors[:4]
+        T, kvf, qf = cfg["T"], cfg["kv_frames"], cfg["q_frames"]
+        rows = wl.sample_rows(T, qf, 2 if qf * T > 20000 else 6, cfg["seed"])
+        host = lambda t: t.float().cpu().numpy().astype(np.float64)
+        torch.cuda.synchronize()
+        ref = orc.block_causal_attn(host(q), host(k[:, :, : kvf * T]), host(v[:, :, : kvf * T]), T, kv_frames=kvf, q_frames=qf, rows=rows)
+        got = host(out[:, :, torch.from_numpy(rows).to(out.device)])
+        d = got - ref
+        row = np.sqrt((d ** 2).sum(-1)) / np.sqrt((ref ** 2).sum(-1))
+        return dict(max_abs=float(np.abs(d).max()), rel_l2=float(np.linalg.norm(d) / np.linalg.norm(ref)),
+                    worst_row_rel_l2=float(row.max()), rows_per_head=int(len(rows)), finite=bool(np.isfinite(got).all()))
 
     def time_workload(name, steps, warmup, kv8=False):
         cfg = wl.CONFIGS[name] if name in wl.CONFIGS else wl.EXTRA_CONFIGS[name]
@@ -93,8 +114,19 @@ def main():
                 nb.nfd_kvcache_append(attn.h, k, v, kn, vn, B, H, F, T, D, kvf - qf, qf)
             nb.nfd_block_causal_attn_fwd(attn.h, q, k, v, out, B, H, F, T, D, kvf, qf)
 
+        w0, w1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        w0.record()
         for i in range(warmup):
             step(i)
+        warm = warmup
+        while args.settle_ms > 0:  # untimed: let clock and power management settle under this very load
+            w1.record()
+            torch.cuda.synchronize()
+            if w0.elapsed_time(w1) >= args.settle_ms:
+                break
+            for i in range(max(1, warmup)):
+                step(warm + i)
+            warm += max(1, warmup)
         torch.cuda.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
@@ -111,11 +143,17 @@ def main():
             a1.record()
         torch.cuda.synchronize()
         per = sorted(a0.elapsed_time(a1) for a0, a1 in evs)
+        check = None  # after all timing: the oracle runs on the host and the GPU idles meanwhile
+        if not args.no_check and not kv8:
+            check = oracle_check(sets[(steps - 1) % rotate], cfg)
         flops = nb.unmasked_flops(B, H, D, T, kvf, qf)
         min_bytes = (2 * kvf * T + 2 * qf * T) * D * 2 * B * H
+        # which roof binds: the larger of the times the algorithmic FLOPs and the minimum HBM bytes need at the peaks
+        t_mfma, t_hbm = flops / (PEAK_BF16_TFLOPS * 1e9), min_bytes / (PEAK_HBM_GBS * 1e6)  # ms
         return dict(workload=name, ms_per_step=ms, ms_median=per[len(per) // 2], ms_min=per[0], tflops=flops / ms * 1e-9, gbs=min_bytes / ms * 1e-6,
-                    frames_per_s=B * qf / ms * 1e3, flops=flops, min_bytes=min_bytes, cfg=cfg,
-                    cache_sets=rotate, plan=nb.nfd_attn_plan(nb.NFD_BF16, B, H, F, T, D, kvf, qf))
+                    pct_mfma_peak=100 * t_mfma / ms, pct_hbm_peak=100 * t_hbm / ms, bound="mfma" if t_mfma >= t_hbm else "hbm",
+                    frames_per_s=B * qf / ms * 1e3, flops=flops, min_bytes=min_bytes, cfg=cfg, warmup_steps_run=warm,
+                    vs_oracle=check, cache_sets=rotate, plan=nb.nfd_attn_plan(nb.NFD_BF16, B, H, F, T, D, kvf, qf))
 
     main_res = time_workload(args.workload, args.steps, args.warmup)
     cfg = main_res["cfg"]
@@ -296,12 +334,25 @@ def main():
             r["cpu_baseline"] = oracle_rate(r["workload"], min(args.cpu_seconds, 4.0))
             print(json.dumps({"workload": r["workload"], "cpu_baseline": r["cpu_baseline"]}), file=sys.stderr, flush=True)
 
+    # HBM bytes per launch come from rocprofv3 counter runs kept under profiles/, not from this run
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
     if os.path.exists(tpath):
         with open(tpath) as f:
             traffic = json.load(f).get(args.workload, {}).get("bytes_per_launch")
     frac = main_res["tflops"] / PEAK_BF16_TFLOPS
+    hbm_frac = main_res["gbs"] / PEAK_HBM_GBS
+    if main_res["bound"] == "mfma":
+        roof = {"bound": "mfma", "achieved": round(main_res["tflops"], 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                "frac": round(frac, 4)}
+    else:
+        roof = {"bound": "hbm", "achieved": round(main_res["gbs"], 1), "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": round(hbm_frac, 4)}
+    roof.update({"traffic": traffic, "traffic_source": "profiles/hbm_traffic.json (rocprofv3 --pmc runs; not measured in this run)",
+                 "kernel": "attn_fwd_bf16_d64",
+                 # both roofs, always: the algorithmic FLOPs against the matrix-core peak, the minimum bytes against HBM
+                 "mfma": {"achieved_tflops": round(main_res["tflops"], 2), "peak": PEAK_BF16_TFLOPS, "frac": round(frac, 4)},
+                 "hbm": {"achieved_gbs": round(main_res["gbs"], 1), "peak": PEAK_HBM_GBS, "frac": round(hbm_frac, 4),
+                         "min_bytes": main_res["min_bytes"]}})
     line = {
         "metric": "block-causal attn TFLOP/s (unmasked) + % bf16 MFMA peak; attn-layer frames/s",
         "value": round(main_res["tflops"], 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
@@ -309,14 +360,15 @@ def main():
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": args.workload, "B": cfg["B"], "H": cfg["H"], "D": cfg["D"], "T": cfg["T"],
                    "kv_frames": cfg["kv_frames"], "q_frames": cfg["q_frames"],
-                   "pct_bf16_mfma_peak": round(100 * frac, 2),
+                   "pct_bf16_mfma_peak": round(100 * frac, 2), "gbs": round(main_res["gbs"], 1),
+                   "pct_hbm_peak": round(100 * hbm_frac, 2), "bound": main_res["bound"],
+                   "warmup_steps_run": main_res["warmup_steps_run"], "settle_ms": args.settle_ms,
                    "attn_layer_frames_per_s": round(main_res["frames_per_s"], 1),
                    "ms_per_step_median": round(main_res["ms_median"], 5), "ms_per_step_min": round(main_res["ms_min"], 5),
                    "cache_sets": main_res["cache_sets"], "plan": main_res["plan"]},
-        "roofline": {"bound": "mfma", "achieved": round(main_res["tflops"], 2), "peak": PEAK_BF16_TFLOPS,
-                     "unit": "TFLOP/s", "frac": round(frac, 4), "traffic": traffic,
-                     "kernel": "attn_fwd_bf16_d64"},
+        "roofline": roof,
         "cpu_baseline": cpu,
+        "vs_oracle": main_res["vs_oracle"],
     }
     if backward:
         line["backward"] = backward
@@ -326,7 +378,8 @@ def main():
         line["fp8_kv_cache"] = fp8kv
     if others:
         line["other_workloads"] = [{k: (round(v, 4) if isinstance(v, float) else v) for k, v in r.items()
-                                    if k in ("workload", "ms_per_step", "ms_median", "ms_min", "tflops", "gbs", "frames_per_s", "cpu_baseline")}
+                                    if k in ("workload", "ms_per_step", "ms_median", "ms_min", "tflops", "pct_mfma_peak", "gbs", "pct_hbm_peak", "bound",
+                                             "frames_per_s", "vs_oracle", "cpu_baseline")}
                                    for r in others]
     attn.close()
     print(json.dumps(line), flush=True)
