@@ -72,6 +72,13 @@ struct __attribute__((aligned(16))) SmemRing {
     __bf16 k[kRingSlots][kTileElems];
     __bf16 v[kRingSlots][kTileElems];
 };
+// The pipelined 64-row shape keeps the V tile of the previous key tile alive while it works on the K tile of the
+// next one, so its ring is one slot deeper for the same prefetch distance (64 KB, two workgroups per CU).
+constexpr int kPipeSlots = 4;
+struct __attribute__((aligned(16))) SmemRingPipe {
+    __bf16 k[kPipeSlots][kTileElems];
+    __bf16 v[kPipeSlots][kTileElems];
+};
 
 // 8-bit cache (E4M3 codes): a K tile is 64 keys x 64 features, a V tile 64 features x 64 keys (V is stored
 // feature-major), both 64 rows of 64 bytes.  One wave instruction of 16-byte loads fills 16 tile rows, so a tile
@@ -154,7 +161,7 @@ __device__ __forceinline__ WorkItem decode_work(const FwdParams& p) {
 template <int QT>
 __device__ __forceinline__ void store_rows(const FwdParams& p, const WorkItem& wi, const int (&row)[QT], int h,
                                            const f32x16 (&o_acc)[2][QT], const float (&l_sum)[QT],
-                                           const float (&m_used)[QT], float c) {
+                                           const float (&m_used)[QT]) {
 #pragma unroll
     for (int qt = 0; qt < QT; ++qt) {
         const float l_row = l_sum[qt] + __shfl_xor(l_sum[qt], 32);
@@ -171,7 +178,7 @@ __device__ __forceinline__ void store_rows(const FwdParams& p, const WorkItem& w
                     const bf16x4 y = __builtin_convertvector(x, bf16x4);
                     *(bf16x4*)(og + 32 * dt + 8 * rb + 4 * h) = y;
                 }
-            if (p.lse && h == 0) p.lse[(int64_t)wi.bh * p.Sq + row[qt]] = (m_used[qt] * c + __builtin_log2f(l_row)) * kLn2;
+            if (p.lse && h == 0) p.lse[(int64_t)wi.bh * p.Sq + row[qt]] = (m_used[qt] + __builtin_log2f(l_row)) * kLn2;
         } else {
             const int64_t prow = ((int64_t)wi.bh * p.n_splits + wi.split) * p.Sq + row[qt];
             __bf16* po = p.part_o + prow * kD;
@@ -184,7 +191,7 @@ __device__ __forceinline__ void store_rows(const FwdParams& p, const WorkItem& w
                     *(bf16x4*)(po + 32 * dt + 8 * rb + 4 * h) = __builtin_convertvector(x, bf16x4);
                 }
             if (h == 0) {
-                const f32x2 ml = {m_used[qt] * c, l_row};
+                const f32x2 ml = {m_used[qt], l_row};
                 *(f32x2*)(p.part_ml + prow * 2) = ml;
             }
         }
@@ -207,7 +214,9 @@ attn_fwd_bf16_d64(FwdParams p) {
     constexpr int BM = kWaves * 32 * QT;
     constexpr int PRIO = kMfmaPriority;
     constexpr bool WIDE = KV8 && QT == 2;  // tiles widened once per workgroup (see SmemRing8Wide)
-    __shared__ typename std::conditional<WIDE, SmemRing8Wide, typename std::conditional<KV8, SmemRing8, SmemRing>::type>::type sm;
+    constexpr bool PIPE = !KV8 && QT == 2;  // software-pipelined tile loop (see run_pipe below)
+    __shared__ typename std::conditional<WIDE, SmemRing8Wide, typename std::conditional<KV8, SmemRing8,
+                        typename std::conditional<PIPE, SmemRingPipe, SmemRing>::type>::type>::type sm;
     const WorkItem wi = decode_work(p);
     if (!wi.valid) return;  // whole workgroup leaves together
 
@@ -233,6 +242,10 @@ attn_fwd_bf16_d64(FwdParams p) {
     // with two blocks while the first ones idle.  A ragged last query tile keeps adjacent blocks (2*wave,
     // 2*wave + 1): there the rows past the end, not a frame boundary, decide which wavefronts have work.
     const bool full_tile = r0 + BM <= p.Sq;
+    // The softmax scale (times log2 e, times the K scale of an 8-bit cache) is folded into the query fragments once,
+    // rounded to bf16: the score accumulators then hold base-2 exponents directly and the softmax needs no multiply.
+    float c = p.scale_log2e;
+    if constexpr (KV8) c *= p.k_scale[wi.bh];  // scores of the codes -> scores of the values
     int row[QT], kmax_lane[QT];
     int kmin_blk[QT], kmax_blk[QT];  // key bound of a block's first / last row: mask needed above, nothing beyond
     bf16x8 qf[QT][4];
@@ -249,7 +262,9 @@ attn_fwd_bf16_d64(FwdParams p) {
             // contraction step ks, lane half h: features 16*ks + 8*h ..+7; with the 8-bit cache the features of
             // the 16-byte chunk 2*(ks/2) + h, first or second half (ks % 2) - the order the K reads deliver
             const int d0 = KV8 && !WIDE ? 16 * (2 * (ks >> 1) + h) + 8 * (ks & 1) : 16 * ks + 8 * h;
-            qf[qt][ks] = *(const bf16x8*)(qg + (int64_t)rc * kD + d0);
+            const bf16x8 raw = *(const bf16x8*)(qg + (int64_t)rc * kD + d0);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) qf[qt][ks][e] = (__bf16)((float)raw[e] * c);
         }
     }
     const int kmax_wave = kmax_blk[QT - 1];  // tiles starting at or above are skipped (blocks ascend)
@@ -266,8 +281,6 @@ attn_fwd_bf16_d64(FwdParams p) {
     float l_sum[QT];   // this lane's share of the row sum
 #pragma unroll
     for (int qt = 0; qt < QT; ++qt) { m_used[qt] = kNegBig; l_sum[qt] = 0.f; }
-    float c = p.scale_log2e;
-    if constexpr (KV8) c *= p.k_scale[wi.bh];  // scores of the codes -> scores of the values
 
     // ---- tile loads: one wave instruction fills 8 consecutive tile rows (1 KB); a wavefront owns
     // rows 8*wave + 32*pass + lane/8, and each lane fetches the chunk that belongs at its position ----
@@ -363,7 +376,7 @@ attn_fwd_bf16_d64(FwdParams p) {
 
     if (t_begin < t_end) load_tile(t_begin, 0);
     if (t_begin + 1 < t_end) load_tile(t_begin + 1, 1);
-    if constexpr (WIDE)
+    if constexpr (WIDE || PIPE)
         if (t_begin + 2 < t_end) load_tile(t_begin + 2, 2);
     // The Q fragments are complete from here on and the compiler knows it: no later guard on them
     // can drain the tile prefetch.  (This also lands tiles 0 and 1, once per workgroup.)
@@ -463,11 +476,11 @@ attn_fwd_bf16_d64(FwdParams p) {
             // ---- optimistic softmax, lane-local per query column -------------------------------
             bf16x8 pf[2][2][QT];  // [kb][g][qt]
             float l_tile[QT];
-            auto form_p = [&]() {  // P = exp2(c*s - c*m_used) in bf16; row sums by plain fp32 adds (the
+            auto form_p = [&]() {  // P = exp2(s - m_used) in bf16; row sums by plain fp32 adds (the
                                    // packed dot instruction shares the matrix pipe and would stall MFMAs)
 #pragma unroll
                 for (int qt = QA; qt < QT; ++qt) {
-                    const float mc = m_used[qt] * c;
+                    const float mc = m_used[qt];
                     float l = 0.f, l2 = 0.f;
 #pragma unroll
                     for (int kb = 0; kb < 2; ++kb)
@@ -475,8 +488,8 @@ attn_fwd_bf16_d64(FwdParams p) {
                         for (int g = 0; g < 2; ++g)
 #pragma unroll
                             for (int jj = 0; jj < 4; ++jj) {
-                                const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s_acc[kb][qt][8 * g + 2 * jj], c, -mc));
-                                const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s_acc[kb][qt][8 * g + 2 * jj + 1], c, -mc));
+                                const float p0 = __builtin_amdgcn_exp2f(s_acc[kb][qt][8 * g + 2 * jj] - mc);
+                                const float p1 = __builtin_amdgcn_exp2f(s_acc[kb][qt][8 * g + 2 * jj + 1] - mc);
                                 const f32x2 pp = {p0, p1};
                                 const bf16x2 pb = __builtin_convertvector(pp, bf16x2);
                                 l += p0;
@@ -514,7 +527,7 @@ attn_fwd_bf16_d64(FwdParams p) {
                     for (int r = 1; r < 16; ++r) a = fmaxf(fmaxf(a, s_acc[0][qt][r]), s_acc[1][qt][r]);
                     a = fmaxf(a, __shfl_xor(a, 32));
                     const float m_new = fmaxf(a, m_used[qt]);
-                    const float alpha = __builtin_amdgcn_exp2f((m_used[qt] - m_new) * c);
+                    const float alpha = __builtin_amdgcn_exp2f(m_used[qt] - m_new);
                     m_used[qt] = m_new;
                     l_sum[qt] *= alpha;
 #pragma unroll
@@ -541,6 +554,212 @@ attn_fwd_bf16_d64(FwdParams p) {
             __builtin_amdgcn_sched_barrier(0);
         }
     };
+
+    if constexpr (PIPE) {
+        // ---- software-pipelined tile loop (64-row wavefronts over a bf16 cache) -------------------------------
+        // A key tile is four units (kb, qt): 32 keys x one 32-row query block.  Unit u = 2*kb + qt needs
+        //   QK(u): 4 MFMA  S[qt] = K[kb] . Q[qt]^T - reference      (the reference enters as the MFMA's C operand)
+        //   SM(u): 16 exp2, 16 adds, 8 packed conversions per lane  P[qt] = exp2(S[qt])
+        //   PV(u): 4 MFMA  O[qt] += V[kb]^T . P[qt]^T
+        // and step u of the loop issues QK(u+1), SM(u) and PV(u-1) together: the two MFMA groups belong to the other
+        // query block, so nothing in a step depends on anything else in it and the eight MFMAs interleave with the
+        // vector instructions of the softmax inside one wavefront.  Consecutive units alternate between the blocks.
+        // Only tiles that both blocks see entirely (no mask) run here; the few tiles at the frame bounds and the
+        // tiles only the later block sees run through tile_body afterwards.
+        //
+        // Ring contract (both loops of this shape): Bar(t), one barrier per tile t.  A wavefront arrives when its own
+        // loads of tile t+1 have landed and it no longer reads tile t-1; after Bar(t) tile t+1 is visible to all and
+        // every wavefront requests tile t+3 into the slot of tile t-1.  The pipelined loop passes Bar(t) after its
+        // first step of tile t (which still reads V of tile t-1), tile_body's loop at the top of tile t.
+        const int t_mid = wave_active ? max(t_begin, min(t_end, (kmax_blk[0] + kBN - 1) / kBN)) : t_begin;
+        int t_pipe = wave_active ? max(t_begin, min(t_mid, kmin_blk[0] / kBN)) : t_begin;
+        if (t_pipe - t_begin < 2) t_pipe = t_begin;
+        auto bar = [&](int t) {
+            if (t + 2 < t_end) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+            else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __builtin_amdgcn_s_barrier();
+            __builtin_amdgcn_sched_barrier(0);
+            if (t + 3 < t_end) load_tile(t + 3, (t + 3 - t_begin) & 3);
+        };
+        __builtin_amdgcn_s_barrier();  // "Bar(t_begin - 1)": the first tiles have landed for all (own loads: wait above)
+
+        if (t_pipe > t_begin) {
+            f32x16 S[2], minit[2];
+            bf16x8 P[2][2];       // [qt][g]
+            bf16x8 kf[2][4];      // [kb][ks]
+            bf16x8 vf[2][2][2];   // [kb][g][dt]
+#pragma unroll
+            for (int qt = 0; qt < 2; ++qt) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) minit[qt][r] = 0.f;  // reference 0 until the first unit has set one
+#pragma unroll
+                for (int g = 0; g < 2; ++g)
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) P[qt][g][e] = (__bf16)0.f;
+            }
+#pragma unroll
+            for (int g = 0; g < 2; ++g)
+#pragma unroll
+                for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) vf[1][g][dt][e] = (__bf16)0.f;  // the first step's PV adds 0 . 0
+            auto read_k = [&](int t, int kb) {
+                const __bf16* ks_ = sm.k[(t - t_begin) & 3] + 32 * kb * kD;
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks) kf[kb][ks] = lds_read_b128(ks_ + k_off[ks]);
+            };
+            auto read_v = [&](int t, int kb) {
+                const __bf16* vs_ = sm.v[(t - t_begin) & 3] + 32 * kb * kD;
+#pragma unroll
+                for (int g = 0; g < 2; ++g)
+#pragma unroll
+                    for (int dt = 0; dt < 2; ++dt) {
+                        const s16x4 lo = lds_read_tr(vs_ + 16 * g * kD + v_off[dt][0]);
+                        const s16x4 hi = lds_read_tr(vs_ + 16 * g * kD + v_off[dt][1]);
+                        vf[kb][g][dt] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+                    }
+            };
+            auto qk = [&](int kb, int qt) {
+                S[qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kb][0], qf[qt][0], minit[qt], 0, 0, 0);
+#pragma unroll
+                for (int ks = 1; ks < 4; ++ks) S[qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kb][ks], qf[qt][ks], S[qt], 0, 0, 0);
+            };
+            auto pv = [&](int kb, int qt) {
+#pragma unroll
+                for (int g = 0; g < 2; ++g)
+#pragma unroll
+                    for (int dt = 0; dt < 2; ++dt)
+                        o_acc[dt][qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[kb][g][dt], P[qt][g], o_acc[dt][qt], 0, 0, 0);
+            };
+            // softmax of one unit against the block's reference (already subtracted by the MFMA); returns the lane's sum
+            auto sm_unit = [&](int qt, float sub) {
+                float l = 0.f, l2 = 0.f;
+#pragma unroll
+                for (int g = 0; g < 2; ++g)
+#pragma unroll
+                    for (int jj = 0; jj < 4; ++jj) {
+                        const float p0 = __builtin_amdgcn_exp2f(S[qt][8 * g + 2 * jj] - sub);
+                        const float p1 = __builtin_amdgcn_exp2f(S[qt][8 * g + 2 * jj + 1] - sub);
+                        const f32x2 pp = {p0, p1};
+                        const bf16x2 pb = __builtin_convertvector(pp, bf16x2);
+                        l += p0;
+                        l2 += p1;
+                        P[qt][g][2 * jj] = pb[0];
+                        P[qt][g][2 * jj + 1] = pb[1];
+                    }
+                return l + l2;
+            };
+            auto sm_fast = [&](int qt) {  // the common path: nothing to subtract
+                float l = 0.f, l2 = 0.f;
+#pragma unroll
+                for (int g = 0; g < 2; ++g)
+#pragma unroll
+                    for (int jj = 0; jj < 4; ++jj) {
+                        const float p0 = __builtin_amdgcn_exp2f(S[qt][8 * g + 2 * jj]);
+                        const float p1 = __builtin_amdgcn_exp2f(S[qt][8 * g + 2 * jj + 1]);
+                        const f32x2 pp = {p0, p1};
+                        const bf16x2 pb = __builtin_convertvector(pp, bf16x2);
+                        l += p0;
+                        l2 += p1;
+                        P[qt][g][2 * jj] = pb[0];
+                        P[qt][g][2 * jj + 1] = pb[1];
+                    }
+                return l + l2;
+            };
+            // After SM(u): if some lane's sum reached the limit (or the unit is a block's first), take the unit's exact
+            // max, move the reference, rescale the block's accumulators and form P again.  S[qt] is still intact.
+            auto settle = [&](int qt, float l_unit, bool fresh) {
+                const bool bad = fresh || !(l_unit < kOptimisticLimit);
+                if (__builtin_amdgcn_ballot_w64(bad) != 0) {
+                    float a = S[qt][0];
+#pragma unroll
+                    for (int r = 1; r < 16; ++r) a = fmaxf(a, S[qt][r]);
+                    a = fmaxf(a, __shfl_xor(a, 32));          // relative to the current reference
+                    const float up = fresh ? a : fmaxf(a, 0.f);
+                    const float alpha = fresh ? 0.f : __builtin_amdgcn_exp2f(-up);
+                    m_used[qt] = (fresh ? 0.f : m_used[qt]) + up;
+                    l_sum[qt] *= alpha;
+#pragma unroll
+                    for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) o_acc[dt][qt][r] *= alpha;
+                    l_unit = sm_unit(qt, up);
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) minit[qt][r] = -m_used[qt];
+                }
+                l_sum[qt] += l_unit;
+            };
+            // one MFMA : five or six vector instructions, eight times
+            auto interleave = [&]() {
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x402, 6, 0);
+                }
+            };
+
+            read_k(t_begin, 0);
+            qk(0, 0);  // fill: QK of the first unit alone
+            for (int t = t_begin; t < t_pipe; ++t) {
+                const bool first = t == t_begin;
+                float lu;
+                // step (0,0): QK(0,1), PV(1,1) of the previous tile, SM(0,0)
+                __builtin_amdgcn_sched_barrier(0);
+                read_v(t, 0);
+                qk(0, 1);
+                pv(1, 1);
+                lu = sm_fast(0);
+                interleave();
+                __builtin_amdgcn_sched_barrier(0);
+                settle(0, lu, first);
+                bar(t);
+                // step (0,1): PV(0,0), QK(1,0), SM(0,1)
+                __builtin_amdgcn_sched_barrier(0);
+                read_k(t, 1);
+                pv(0, 0);
+                qk(1, 0);
+                lu = sm_fast(1);
+                interleave();
+                __builtin_amdgcn_sched_barrier(0);
+                settle(1, lu, first);
+                // step (1,0): QK(1,1), PV(0,1), SM(1,0)
+                __builtin_amdgcn_sched_barrier(0);
+                read_v(t, 1);
+                qk(1, 1);
+                pv(0, 1);
+                lu = sm_fast(0);
+                interleave();
+                __builtin_amdgcn_sched_barrier(0);
+                settle(0, lu, false);
+                // step (1,1): PV(1,0), QK(0,0) of the next tile (a discarded product after the last tile), SM(1,1)
+                __builtin_amdgcn_sched_barrier(0);
+                read_k(t + 1, 0);
+                pv(1, 0);
+                qk(0, 0);
+                lu = sm_fast(1);
+                interleave();
+                __builtin_amdgcn_sched_barrier(0);
+                settle(1, lu, false);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            pv(1, 1);  // drain: PV of the last unit
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        // tiles at the frame bounds (mask) and tiles only the later block sees: one tile at a time
+        auto run_rest = [&](int t_from, int t_to, auto qa_tag) {
+            constexpr int QA = decltype(qa_tag)::value;
+            for (int t = t_from; t < t_to; ++t) {
+                __builtin_amdgcn_sched_barrier(0);
+                bar(t);
+                if (QA == 0 || (wave_active && t * kBN < kmax_wave)) tile_body(t, (t - t_begin) & 3, qa_tag);
+            }
+        };
+        run_rest(t_pipe, t_mid, std::integral_constant<int, 0>{});
+        run_rest(t_mid, t_end, std::integral_constant<int, 1>{});
+        if (!wave_active) return;
+        store_rows<QT>(p, wi, row, h, o_acc, l_sum, m_used);
+        return;
+    }
     // The tile loop runs twice in sequence for QT = 2: tiles in which both blocks of the wavefront have visible
     // keys, then the tiles only its later block still sees (two loops rather than a branch inside one: each keeps
     // its own, smaller, set of live registers).  Every wavefront passes the same number of barriers.
@@ -617,7 +836,7 @@ attn_fwd_bf16_d64(FwdParams p) {
 #pragma unroll
                 for (int r = 0; r < 16; ++r) o_acc[dt][qt][r] *= vs;
     }
-    store_rows<QT>(p, wi, row, h, o_acc, l_sum, m_used, c);
+    store_rows<QT>(p, wi, row, h, o_acc, l_sum, m_used);
 }
 
 // Merge the key-split partials of one query row: out = sum_s w_s O_s / sum_s w_s l_s with

@@ -9,7 +9,7 @@ import numpy as np
 BF16_MAX_ABS, BF16_REL_L2, FP32_MAX_ABS = 2e-2, 1e-2, 1e-4
 BF16_REL_L2_INTERNAL = 5e-3
 # |g_i - o_i|_2 / |o_i|_2 for every query row i; about three times the worst row measured over all GPU tests
-BF16_ROW_REL_L2 = 1.5e-2  # worst row measured: 4.8e-3 (c2 at full size), 4.7e-3 (rising scores)
+BF16_ROW_REL_L2 = 2.5e-2  # worst row measured: 8.6e-3 (16-frame training form, 12 heads), 7.6e-3 (c2 at full size)
 
 
 def row_errors(got, ref):
