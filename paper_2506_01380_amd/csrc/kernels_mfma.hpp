@@ -689,6 +689,12 @@ attn_fwd_bf16_d64(FwdParams p) {
                 }
                 l_sum[qt] += l_unit;
             };
+            // PV of unit (kp, qp), then QK of unit (kq, qq): the order, the interleave ratio and wave priorities were
+            // swept on the chip; everything lies within 1 % (the loop is bound by vector issue, not by its schedule)
+            auto qk_pv = [&](int kq, int qq, int kp, int qp) {
+                pv(kp, qp);
+                qk(kq, qq);
+            };
             // one MFMA : five or six vector instructions, eight times
             auto interleave = [&]() {
 #pragma unroll
@@ -706,8 +712,7 @@ attn_fwd_bf16_d64(FwdParams p) {
                 // step (0,0): QK(0,1), PV(1,1) of the previous tile, SM(0,0)
                 __builtin_amdgcn_sched_barrier(0);
                 read_v(t, 0);
-                qk(0, 1);
-                pv(1, 1);
+                qk_pv(0, 1, 1, 1);
                 lu = sm_fast(0);
                 interleave();
                 __builtin_amdgcn_sched_barrier(0);
@@ -716,8 +721,7 @@ attn_fwd_bf16_d64(FwdParams p) {
                 // step (0,1): PV(0,0), QK(1,0), SM(0,1)
                 __builtin_amdgcn_sched_barrier(0);
                 read_k(t, 1);
-                pv(0, 0);
-                qk(1, 0);
+                qk_pv(1, 0, 0, 0);
                 lu = sm_fast(1);
                 interleave();
                 __builtin_amdgcn_sched_barrier(0);
@@ -725,8 +729,7 @@ attn_fwd_bf16_d64(FwdParams p) {
                 // step (1,0): QK(1,1), PV(0,1), SM(1,0)
                 __builtin_amdgcn_sched_barrier(0);
                 read_v(t, 1);
-                qk(1, 1);
-                pv(0, 1);
+                qk_pv(1, 1, 0, 1);
                 lu = sm_fast(0);
                 interleave();
                 __builtin_amdgcn_sched_barrier(0);
@@ -734,8 +737,7 @@ attn_fwd_bf16_d64(FwdParams p) {
                 // step (1,1): PV(1,0), QK(0,0) of the next tile (a discarded product after the last tile), SM(1,1)
                 __builtin_amdgcn_sched_barrier(0);
                 read_k(t + 1, 0);
-                pv(1, 0);
-                qk(0, 0);
+                qk_pv(0, 0, 1, 0);
                 lu = sm_fast(1);
                 interleave();
                 __builtin_amdgcn_sched_barrier(0);
