@@ -3,7 +3,7 @@
 
 One "step" is one pass of the hot path over one batch of synthetic input: for the
 training form the forward call; for the cached forms the cache append of the new
-frames followed by the forward call.  Inputs are resident in HBM before the timed
+frames and the forward over the cache (nfd_kvcache_append_attn_fwd: one call).  Inputs are resident in HBM before the timed
 region.  Prints ONE JSON line on stdout.
 """
 import argparse
@@ -110,9 +110,10 @@ def main():
                 nb.nfd_kvcache_append_fp8(attn.h, k, v, ksc, vsc, kn, vn, B, H, F, T, D, kvf - qf, qf)
                 nb.nfd_block_causal_attn_fwd_fp8kv(attn.h, q, k, v, ksc, vsc, out, B, H, F, T, D, kvf, qf)
                 return
-            if cached:
-                nb.nfd_kvcache_append(attn.h, k, v, kn, vn, B, H, F, T, D, kvf - qf, qf)
-            nb.nfd_block_causal_attn_fwd(attn.h, q, k, v, out, B, H, F, T, D, kvf, qf)
+            if cached:  # cache write of the new frames and the attention over the cache, one call
+                nb.nfd_kvcache_append_attn_fwd(attn.h, q, k, v, kn, vn, out, B, H, F, T, D, kvf, qf)
+            else:
+                nb.nfd_block_causal_attn_fwd(attn.h, q, k, v, out, B, H, F, T, D, kvf, qf)
 
         w0, w1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         w0.record()

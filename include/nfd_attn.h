@@ -83,6 +83,23 @@ int nfd_block_causal_attn_fwd(nfd_attn_t* h, const void* q, const void* k, const
                               float scale, void* stream);
 
 /*
+ * One call for a cached step (Appendix B "KV Caching"; Sec. 4.2 for q_frames > 1): write the K/V of the q_frames
+ * newest frames into the cache and attend.  Same result, bit for bit, in out and in the caches as
+ *   nfd_kvcache_append(h, k_cache, v_cache, k_new, v_new, ..., frame_pos = kv_frames - q_frames, n_frames = q_frames)
+ *   nfd_block_causal_attn_fwd(h, q, k_cache, v_cache, out, ..., kv_frames, q_frames)
+ * but for bf16 with D = 64 in ONE launch: the attention reads the new frames' keys and values from k_new / v_new
+ * where they are, and its workgroups copy them into the cache on the side (nothing in the launch reads the cache
+ * rows that are being written).  Other dtypes / head widths, and calls with too few workgroups for the copy, run
+ * the two launches.
+ *   q, out : [B, H, q_frames*T, D]     k_new, v_new : [B, H, q_frames*T, D] (must not overlap the caches)
+ *   k_cache, v_cache : [B, H, F*T, D]; frames [kv_frames - q_frames, kv_frames) of every head are overwritten
+ * Errors as for nfd_block_causal_attn_fwd, plus NFD_ERR_NULL for k_new / v_new.
+ */
+int nfd_kvcache_append_attn_fwd(nfd_attn_t* h, const void* q, void* k_cache, void* v_cache, const void* k_new,
+                                const void* v_new, void* out, int B, int H, int F, int T, int D, int kv_frames,
+                                int q_frames, float scale, void* stream);
+
+/*
  * nfd_block_causal_attn_fwd for callers that cannot allocate device memory and therefore cannot create a
  * handle: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  No handle;
  * the key-split partials, which the handle version keeps in its workspace, go to a fixed array of

@@ -27,7 +27,7 @@ EXPORTS = (
     "nfd_rope_kvcache_append", "nfd_rope_check_args",
     "nfd_block_causal_attn_fwd_lse", "nfd_block_causal_attn_bwd",
     "nfd_kvcache_shift", "nfd_spec_init", "nfd_spec_next", "nfd_spec_accept", "nfd_attn_work_item",
-    "nfd_block_causal_attn_fwd_noalloc",
+    "nfd_block_causal_attn_fwd_noalloc", "nfd_kvcache_append_attn_fwd",
     "nfd_fp8_cache_bytes", "nfd_kvcache_append_fp8", "nfd_block_causal_attn_fwd_fp8kv", "nfd_kvcache_shift_fp8", "nfd_rope_kvcache_append_fp8",
 )
 
@@ -81,6 +81,8 @@ def lib():
         L.nfd_block_causal_attn_fwd.restype = ci
         L.nfd_block_causal_attn_fwd_noalloc.argtypes = [ci, vp, vp, vp, vp] + [ci] * 7 + [cf, vp, ctypes.c_char_p, ctypes.c_size_t]
         L.nfd_block_causal_attn_fwd_noalloc.restype = ci
+        L.nfd_kvcache_append_attn_fwd.argtypes = [vp] * 7 + [ci] * 7 + [cf, vp]
+        L.nfd_kvcache_append_attn_fwd.restype = ci
         L.nfd_block_causal_attn_fwd_lse.argtypes = [vp] * 6 + [ci] * 7 + [cf, vp]
         L.nfd_block_causal_attn_fwd_lse.restype = ci
         L.nfd_block_causal_attn_bwd.argtypes = [vp] * 10 + [ci] * 7 + [cf, vp]
@@ -170,6 +172,13 @@ def nfd_block_causal_attn_fwd_noalloc(dtype, q, k, v, out, B, H, F, T, D, kv_fra
                                                  kv_frames, q_frames, scale, _stream(stream), err, len(err))
     if rc != NFD_OK:
         raise NfdError(rc, "nfd_block_causal_attn_fwd_noalloc", err.value.decode())
+
+
+def nfd_kvcache_append_attn_fwd(h, q, k_cache, v_cache, k_new, v_new, out, B, H, F, T, D, kv_frames, q_frames,
+                                scale=0.0, stream=None):
+    rc = lib().nfd_kvcache_append_attn_fwd(h, _addr(q), _addr(k_cache), _addr(v_cache), _addr(k_new), _addr(v_new),
+                                           _addr(out), B, H, F, T, D, kv_frames, q_frames, scale, _stream(stream))
+    _check(rc, "nfd_kvcache_append_attn_fwd", h)
 
 
 def nfd_block_causal_attn_fwd_lse(h, q, k, v, out, lse, B, H, F, T, D, kv_frames, q_frames, scale=0.0, stream=None):

@@ -152,7 +152,13 @@ __host__ __device__ __forceinline__ WorkItem work_item_of(unsigned block, int BH
     return w;
 }
 __device__ __forceinline__ WorkItem decode_work(const FwdParams& p) {
-    return work_item_of(blockIdx.x, p.BH, p.n_q_tiles, p.n_splits, p.group_q_tiles);
+    WorkItem w = work_item_of(blockIdx.x, p.BH, p.n_q_tiles, p.n_splits, p.group_q_tiles);
+    // the divisions run on the vector unit: bring the (uniform) results back to scalar registers, so that everything
+    // derived from them - tensor base pointers above all - is scalar too
+    w.bh = __builtin_amdgcn_readfirstlane(w.bh);
+    w.q_tile = __builtin_amdgcn_readfirstlane(w.q_tile);
+    w.split = __builtin_amdgcn_readfirstlane(w.split);
+    return w;
 }
 
 // Final write of one wavefront's 64 query rows: normalised bf16 output when the keys were not
@@ -234,6 +240,33 @@ attn_fwd_bf16_d64(FwdParams p) {
     const __bf16* qg = (const __bf16*)p.q + (int64_t)wi.bh * p.Sq * kD;
     const __bf16* kg = (const __bf16*)p.k + (int64_t)wi.bh * p.Scap * kD;
     const __bf16* vg = (const __bf16*)p.v + (int64_t)wi.bh * p.Scap * kD;
+    // fused append: the new frames' rows, addressed by cache row index (row Snew0 of the cache is row 0 of k_new)
+    const bool fused = !KV8 && p.k_new != nullptr;
+    const __bf16* kn = fused ? (const __bf16*)p.k_new + ((int64_t)wi.bh * p.Sq - p.Snew0) * kD : kg;
+    const __bf16* vn = fused ? (const __bf16*)p.v_new + ((int64_t)wi.bh * p.Sq - p.Snew0) * kD : vg;
+    // This workgroup's share of the copy of k_new, v_new into the cache: 16-byte vectors gid, gid + threads, ...
+    // The loads go out first and land behind the same wait as the query fragments; the stores follow it.
+    constexpr int kMaxCopy = 4;
+    u32x4 cp_k[kMaxCopy], cp_v[kMaxCopy];
+    int64_t cp_dst[kMaxCopy];
+    if constexpr (!KV8) {
+        if (fused) {
+            const int64_t n_vec = (int64_t)p.BH * p.Sq * (kD / 8), n_thr = (int64_t)gridDim.x * blockDim.x;
+            const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+#pragma unroll
+            for (int i = 0; i < kMaxCopy; ++i) {
+                const int64_t x = gid + i * n_thr;
+                cp_dst[i] = -1;
+                if (x < n_vec) {
+                    const int64_t per_head = (int64_t)p.Sq * (kD / 8);
+                    const int64_t bh = x / per_head, rem = x - bh * per_head;
+                    cp_dst[i] = (bh * p.Scap + p.Snew0) * (kD / 8) + rem;
+                    cp_k[i] = ((const u32x4*)p.k_new)[x];
+                    cp_v[i] = ((const u32x4*)p.v_new)[x];
+                }
+            }
+        }
+    }
 
     // ---- this wavefront's queries -------------------------------------------------------
     // QT = 2: the wavefront owns the 32-row blocks `wave` and `wave + 4` of the workgroup's 256 rows, not two
@@ -286,6 +319,8 @@ attn_fwd_bf16_d64(FwdParams p) {
     // rows 8*wave + 32*pass + lane/8, and each lane fetches the chunk that belongs at its position ----
     const int ld_row = 8 * wave + (lane >> 3);
     const int ld_chunk = (lane & 7) ^ chunk_swizzle(ld_row);  // rows +32: same swizzle
+    const unsigned ld_voff[2] = {(unsigned)(ld_row * kD + ld_chunk * 8) * 2u, (unsigned)((ld_row + 32) * kD + ld_chunk * 8) * 2u};  // bytes
+    const int ld_plain_end = min(p.Sk, p.Snew0);  // tiles that end at or below: whole, and in the cache
     const unsigned lds_k0 = (unsigned)(size_t)(__attribute__((address_space(3))) char*)(&sm.k[0][0]) + wave * 1024;
     const unsigned lds_v0 = (unsigned)(size_t)(__attribute__((address_space(3))) char*)(&sm.v[0][0]) + wave * 1024;
     // 8-bit cache: one instruction fills 16 tile rows of 64 bytes; the tensors are padded to whole tiles, so no
@@ -305,14 +340,31 @@ attn_fwd_bf16_d64(FwdParams p) {
         // Issued through inline assembly on purpose: for the builtin the compiler guards every later
         // LDS read and every barrier with vmcnt(0), which would cancel the prefetch distance.  The
         // waits that order these loads are the explicit ones at the top of the tile loop.
+        if ((t + 1) * kBN <= ld_plain_end) {
+            // A whole tile of the cache: scalar base + one precomputed 32-bit lane offset, no vector arithmetic at all
+            // (the tile loop is bound by vector issue).
+            const __bf16* kt = kg + (int64_t)t * kTileElems;
+            const __bf16* vt = vg + (int64_t)t * kTileElems;
+#pragma unroll
+            for (int pass = 0; pass < 2; ++pass) {
+                const unsigned kdst = lds_k0 + (unsigned)(slot * kTileElems * 2 + pass * 4096);
+                const unsigned vdst = lds_v0 + (unsigned)(slot * kTileElems * 2 + pass * 4096);
+                asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(ld_voff[pass]), "s"(kt), "s"(kdst) : "memory", "m0");
+                asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(ld_voff[pass]), "s"(vt), "s"(vdst) : "memory", "m0");
+            }
+            return;
+        }
+        // The last tile of the cache (rows past the end are clamped: they are masked anyway) and, with a fused append,
+        // the tiles that hold new rows (read from k_new / v_new): one address per lane.
 #pragma unroll
         for (int pass = 0; pass < 2; ++pass) {
             const int kr = min(t * kBN + 32 * pass + ld_row, p.Sk - 1);
             const int64_t off = (int64_t)kr * kD + ld_chunk * 8;
+            const bool from_new = kr >= p.Snew0;  // never true without a fused append (Snew0 = INT_MAX then)
             const unsigned kdst = lds_k0 + (unsigned)(slot * kTileElems * 2 + pass * 4096);
             const unsigned vdst = lds_v0 + (unsigned)(slot * kTileElems * 2 + pass * 4096);
-            asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(kg + off), "s"(kdst) : "memory", "m0");
-            asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(vg + off), "s"(vdst) : "memory", "m0");
+            asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"((from_new ? kn : kg) + off), "s"(kdst) : "memory", "m0");
+            asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"((from_new ? vn : vg) + off), "s"(vdst) : "memory", "m0");
         }
     };
 
@@ -381,6 +433,16 @@ attn_fwd_bf16_d64(FwdParams p) {
     // The Q fragments are complete from here on and the compiler knows it: no later guard on them
     // can drain the tile prefetch.  (This also lands tiles 0 and 1, once per workgroup.)
     wait_vmem_all();
+    if constexpr (!KV8) {
+        if (fused) {
+#pragma unroll
+            for (int i = 0; i < kMaxCopy; ++i)
+                if (cp_dst[i] >= 0) {
+                    ((u32x4*)p.k)[cp_dst[i]] = cp_k[i];
+                    ((u32x4*)p.v)[cp_dst[i]] = cp_v[i];
+                }
+        }
+    }
 
     // QA = first block of the wavefront that still has visible keys in this tile (1: its earlier block is done)
     auto tile_body = [&](int t, int slot, auto qa_tag) {

@@ -228,13 +228,20 @@ int nfd_attn_destroy(nfd_attn_t* h) {
 
 const char* nfd_last_error(const nfd_attn_t* h) { return h ? h->err : "null handle"; }
 
+static void launch_frame_copy(nfd_attn_t* h, size_t es, void* kd, void* vd, const void* ks, const void* vs, int64_t BH,
+                              int64_t head_dst, int64_t head_src, int64_t off_dst, int64_t off_src, int64_t len,
+                              hipStream_t st);
+
 // k_scale / v_scale non-null: k and v are the 8-bit caches (see nfd_kvcache_append_fp8).
+// k_new / v_new non-null: the query frames' own K/V, to be appended to the caches k, v by this call (they are written).
 static int fwd_impl(nfd_attn_t* h, const void* q, const void* k, const void* v, void* out, float* lse, int B,
                     int H, int F, int T, int D, int kv_frames, int q_frames, float scale, void* stream,
-                    const float* k_scale = nullptr, const float* v_scale = nullptr) {
+                    const float* k_scale = nullptr, const float* v_scale = nullptr, const void* k_new = nullptr,
+                    const void* v_new = nullptr) {
     if (!h) return NFD_ERR_NULL;
     if (!q || !k || !v || !out) return fail(h, NFD_ERR_NULL, "q, k, v and out must be non-null");
     const bool kv8 = k_scale != nullptr;
+    const bool append = k_new != nullptr;
     nfd_attn_plan_t pl;
     const int rc = nfd_attn_plan(h->dtype, B, H, F, T, D, kv_frames, q_frames, h->num_cus, h->plan_limit, &pl);
     if (rc != NFD_OK) return fail(h, rc, "invalid shape arguments");
@@ -247,6 +254,8 @@ static int fwd_impl(nfd_attn_t* h, const void* q, const void* k, const void* v, 
     if (pl.kernel == 1 && (((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)out) % 16 != 0 || (uintptr_t)lse % 4 != 0))
         return fail(h, NFD_ERR_UNSUPPORTED, "q, k, v, out must be 16-byte aligned (lse 4-byte)");
     if (kv8 && pl.kernel != 1) return fail(h, NFD_ERR_UNSUPPORTED, "the 8-bit cache is built for bf16 queries and head width 64");
+    if (append && pl.kernel == 1 && (((uintptr_t)k_new | (uintptr_t)v_new) % 16 != 0))
+        return fail(h, NFD_ERR_UNSUPPORTED, "k_new and v_new must be 16-byte aligned");
     if (!(scale > 0.f)) scale = 1.0f / std::sqrt((float)D);
 
     nfd::FwdParams p{};
@@ -266,6 +275,21 @@ static int fwd_impl(nfd_attn_t* h, const void* q, const void* k, const void* v, 
     // K and V of all heads against the 256 MB last-level cache (with room for Q, O and partials)
     p.group_q_tiles = pl.n_splits > 1 && (double)p.BH * p.Sk * nfd::mfma::kD * 2.0 * (kv8 ? 1.0 : 2.0) > 192e6;
     p.scale_log2e = scale * nfd::kLog2e;
+    p.Snew0 = 0x7fffffff;
+    if (append) {
+        // In the matrix-core kernel the workgroups read the new rows where they are and copy them into the cache on
+        // the side (at most four 16-byte vectors of each tensor per thread); otherwise a copy launch goes first.
+        const int64_t n_vec = (int64_t)p.BH * p.Sq * (nfd::mfma::kD / 8);
+        if (pl.kernel == 1 && !kv8 && n_vec <= (int64_t)4 * pl.n_workgroups * nfd::mfma::kWaves * 64) {
+            p.k_new = k_new; p.v_new = v_new;
+            p.Snew0 = p.P * T;
+        } else {
+            const int64_t frame_elems = (int64_t)T * D;
+            launch_frame_copy(h, elem_size(h->dtype), const_cast<void*>(k), const_cast<void*>(v), k_new, v_new, (int64_t)B * H,
+                              (int64_t)F * frame_elems, (int64_t)q_frames * frame_elems, (int64_t)p.P * frame_elems, 0,
+                              (int64_t)q_frames * frame_elems, (hipStream_t)stream);
+        }
+    }
     if (pl.n_splits > 1) {
         p.part_o = (__bf16*)h->workspace;
         p.part_ml = (float*)(p.part_o + (size_t)p.BH * pl.n_splits * p.Sq * nfd::mfma::kD);
@@ -359,6 +383,15 @@ int nfd_block_causal_attn_fwd_noalloc(nfd_dtype_t dtype, const void* q, const vo
     // nfd_block_causal_attn_fwd's; a call whose partials do not fit the array is refused (NFD_ERR_ALLOC), not re-planned.
     local.plan_limit = kDefaultWorkspace;
     return done(fwd_impl(&local, q, k, v, out, nullptr, B, H, F, T, D, kv_frames, q_frames, scale, stream));
+}
+
+int nfd_kvcache_append_attn_fwd(nfd_attn_t* h, const void* q, void* k_cache, void* v_cache, const void* k_new,
+                                const void* v_new, void* out, int B, int H, int F, int T, int D, int kv_frames,
+                                int q_frames, float scale, void* stream) {
+    if (!h) return NFD_ERR_NULL;
+    if (!k_new || !v_new) return fail(h, NFD_ERR_NULL, "k_new and v_new must be non-null");
+    return fwd_impl(h, q, k_cache, v_cache, out, nullptr, B, H, F, T, D, kv_frames, q_frames, scale, stream, nullptr, nullptr,
+                    k_new, v_new);
 }
 
 int nfd_block_causal_attn_fwd_lse(nfd_attn_t* h, const void* q, const void* k, const void* v, void* out,

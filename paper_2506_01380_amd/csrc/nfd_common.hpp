@@ -47,6 +47,12 @@ struct FwdParams {
     const float* k_scale;  // [BH]
     const float* v_scale;  // [BH]
     int Spad;              // F * T rounded up to a multiple of 64: row count of k, row length of v
+    // fused cache append (bf16 matrix-core kernels only; null otherwise): the K/V of the query frames themselves,
+    // [BH, Sq, D].  Key rows >= Snew0 = P * T are read from here instead of the cache, and every workgroup copies its
+    // share of these rows into k, v on the side, so the cache ends up as after an append.
+    const void* k_new;
+    const void* v_new;
+    int Snew0;
 };
 
 __device__ __forceinline__ int kmax_of_row(int row, int T, int P) { return (P + row / T + 1) * T; }

@@ -366,3 +366,56 @@ def test_wrapper_methods_validate_their_tensors(attn_bf16):
     with pytest.raises(ValueError):
         attn_bf16.rope_append(mk(B, H, 2 * T, D), k, v, kn, kn, T, 0, (4, 4), (16, 24, 24))  # q and the new frames disagree
     torch.cuda.synchronize()
+
+
+# ---- append fused into the attention launch ---------------------------------------------------------
+@pytest.mark.parametrize("name,B,H,T,D,kvf,qf,F,dtype", [
+    ("c3_decode", None, None, None, None, None, None, None, "bf16"),   # one launch: copy by the attention workgroups
+    ("c4_spec_k4", None, None, None, None, None, None, None, "bf16"),
+    ("c4_spec_k2", None, None, None, None, None, None, None, "bf16"),
+    (None, 2, 3, 40, 64, 9, 3, 11, "bf16"),     # odd frames, spare capacity, heads not a multiple of 8
+    (None, 1, 2, 48, 64, 5, 5, 6, "bf16"),      # no past frames: everything is "new"
+    (None, 1, 1, 16, 64, 40, 39, 40, "bf16"),   # many new rows for few workgroups: the two-launch path
+    (None, 1, 2, 24, 128, 6, 2, 7, "bf16"),     # general kernel (other head width): two launches
+    (None, 1, 2, 16, 64, 4, 1, 4, "fp32"),      # fp32 handle: two launches
+])
+def test_fused_append_equals_append_then_forward(attn_bf16, attn_fp32, name, B, H, T, D, kvf, qf, F, dtype):
+    """nfd_kvcache_append_attn_fwd against the two calls it replaces: out and both caches bit for bit; the rows of
+    the cache that the call overwrites hold NaN beforehand, so reading them would show; and against the oracle."""
+    attn = attn_bf16 if dtype == "bf16" else attn_fp32
+    if name:
+        cfg, q, k, v = wl.make_config(name)
+        B, H, T, D, kvf, qf, F = (cfg[x] for x in ("B", "H", "T", "D", "kv_frames", "q_frames", "F"))
+    else:
+        q, k, v = wl.make_qkv(B, H, D, T, kvf, qf, F, dtype, seed=wl.BASE_SEED + 800 + T + kvf)
+    P = kvf - qf
+    kn, vn = k[:, :, P * T: kvf * T].copy(), v[:, :, P * T: kvf * T].copy()
+    k0, v0 = k.copy(), v.copy()
+    k0[:, :, P * T:] = np.nan   # the new frames' slots and the spare capacity: never to be read
+    v0[:, :, P * T:] = np.nan
+    qd, knd, vnd = to_dev(q, dtype), to_dev(kn, dtype), to_dev(vn, dtype)
+    # two calls
+    ka, va = to_dev(k0, dtype), to_dev(v0, dtype)
+    want = torch.empty_like(qd)
+    nb.nfd_kvcache_append(attn.h, ka, va, knd, vnd, B, H, F, T, D, P, qf)
+    nb.nfd_block_causal_attn_fwd(attn.h, qd, ka, va, want, B, H, F, T, D, kvf, qf)
+    # one call
+    kb, vb = to_dev(k0, dtype), to_dev(v0, dtype)
+    got = torch.full_like(qd, float("nan"))
+    nb.nfd_kvcache_append_attn_fwd(attn.h, qd, kb, vb, knd, vnd, got, B, H, F, T, D, kvf, qf)
+    torch.cuda.synchronize()
+    assert torch.equal(got, want)
+    same = lambda a, b: torch.equal(a.view(torch.int16 if dtype == "bf16" else torch.int32), b.view(torch.int16 if dtype == "bf16" else torch.int32))
+    assert same(ka, kb) and same(va, vb)          # NaN rows past kv_frames compare by bit pattern
+    hk = kb.float().cpu().numpy().astype(np.float64)
+    assert np.array_equal(hk[:, :, : kvf * T], k[:, :, : kvf * T].astype(np.float64))
+    assert np.all(np.isnan(hk[:, :, kvf * T:]))
+    ref = orc.block_causal_attn(q, k, v, T, kv_frames=kvf, q_frames=qf)
+    g = got.float().cpu().numpy().astype(np.float64)
+    if dtype == "bf16":
+        check_bf16(g, ref, "fused append %s" % (name or "B%d H%d T%d D%d" % (B, H, T, D)))
+    else:
+        assert errors(g, ref)[0] <= FP32_MAX_ABS
+    with pytest.raises(nb.NfdError) as e:
+        nb.nfd_kvcache_append_attn_fwd(attn.h, qd, kb, vb, None, vnd, got, B, H, F, T, D, kvf, qf)
+    assert e.value.code == nb.NFD_ERR_NULL
