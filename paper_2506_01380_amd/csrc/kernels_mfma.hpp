@@ -214,7 +214,12 @@ __device__ __forceinline__ void store_rows(const FwdParams& p, const WorkItem& w
 // the operands is the same as for a bf16 cache.  QT = 1: every wavefront widens its own fragments on their way
 // out of LDS (SmemRing8); the feature order inside the first product's contraction is then permuted (a 16-byte
 // read serves two steps), the same way for K and Q.  QT = 2: the workgroup widens each tile once (SmemRing8Wide).
-template <int QT, bool KV8 = false>
+//
+// EXACTQ: the forward of the training pair, which also writes the log-sum-exp the backward normalises with.  The
+// queries enter the first product as given, the scores are exact sums of products of the inputs, and the softmax
+// scale is applied to the fp32 scores (one multiply per score); the reference max is then kept in raw score units.
+// Without it the scale is folded into the query fragments (one more bf16 rounding of an input, no multiply).
+template <int QT, bool KV8 = false, bool EXACTQ = false>
 __global__ void __launch_bounds__(kWaves * 64, QT == 2 ? 2 : 3)
 attn_fwd_bf16_d64(FwdParams p) {
     constexpr int BM = kWaves * 32 * QT;
@@ -296,8 +301,12 @@ attn_fwd_bf16_d64(FwdParams p) {
             // the 16-byte chunk 2*(ks/2) + h, first or second half (ks % 2) - the order the K reads deliver
             const int d0 = KV8 && !WIDE ? 16 * (2 * (ks >> 1) + h) + 8 * (ks & 1) : 16 * ks + 8 * h;
             const bf16x8 raw = *(const bf16x8*)(qg + (int64_t)rc * kD + d0);
+            if constexpr (EXACTQ) {
+                qf[qt][ks] = raw;
+            } else {
 #pragma unroll
-            for (int e = 0; e < 8; ++e) qf[qt][ks][e] = (__bf16)((float)raw[e] * c);
+                for (int e = 0; e < 8; ++e) qf[qt][ks][e] = (__bf16)((float)raw[e] * c);
+            }
         }
     }
     const int kmax_wave = kmax_blk[QT - 1];  // tiles starting at or above are skipped (blocks ascend)
@@ -310,7 +319,8 @@ attn_fwd_bf16_d64(FwdParams p) {
         for (int b = 0; b < QT; ++b)
 #pragma unroll
             for (int r = 0; r < 16; ++r) o_acc[a][b][r] = 0.f;
-    float m_used[QT];  // reference max, raw score units (stale by design)
+    float m_used[QT];  // reference max (stale by design), in the units of the score accumulators: base-2 exponents,
+                       // or raw scores (exponent = c * score) with EXACTQ
     float l_sum[QT];   // this lane's share of the row sum
 #pragma unroll
     for (int qt = 0; qt < QT; ++qt) { m_used[qt] = kNegBig; l_sum[qt] = 0.f; }
@@ -444,6 +454,11 @@ attn_fwd_bf16_d64(FwdParams p) {
         }
     }
 
+    // base-2 exponent of one score against a reference already in exponent units
+    auto to_exponent = [&](float s, float ref_exponent) {
+        if constexpr (EXACTQ) return __builtin_fmaf(s, c, -ref_exponent);
+        else return s - ref_exponent;
+    };
     // QA = first block of the wavefront that still has visible keys in this tile (1: its earlier block is done)
     auto tile_body = [&](int t, int slot, auto qa_tag) {
         constexpr int QA = decltype(qa_tag)::value;
@@ -542,7 +557,7 @@ attn_fwd_bf16_d64(FwdParams p) {
                                    // packed dot instruction shares the matrix pipe and would stall MFMAs)
 #pragma unroll
                 for (int qt = QA; qt < QT; ++qt) {
-                    const float mc = m_used[qt];
+                    const float mc = EXACTQ ? m_used[qt] * c : m_used[qt];
                     float l = 0.f, l2 = 0.f;
 #pragma unroll
                     for (int kb = 0; kb < 2; ++kb)
@@ -550,8 +565,8 @@ attn_fwd_bf16_d64(FwdParams p) {
                         for (int g = 0; g < 2; ++g)
 #pragma unroll
                             for (int jj = 0; jj < 4; ++jj) {
-                                const float p0 = __builtin_amdgcn_exp2f(s_acc[kb][qt][8 * g + 2 * jj] - mc);
-                                const float p1 = __builtin_amdgcn_exp2f(s_acc[kb][qt][8 * g + 2 * jj + 1] - mc);
+                                const float p0 = __builtin_amdgcn_exp2f(to_exponent(s_acc[kb][qt][8 * g + 2 * jj], mc));
+                                const float p1 = __builtin_amdgcn_exp2f(to_exponent(s_acc[kb][qt][8 * g + 2 * jj + 1], mc));
                                 const f32x2 pp = {p0, p1};
                                 const bf16x2 pb = __builtin_convertvector(pp, bf16x2);
                                 l += p0;
@@ -589,7 +604,7 @@ attn_fwd_bf16_d64(FwdParams p) {
                     for (int r = 1; r < 16; ++r) a = fmaxf(fmaxf(a, s_acc[0][qt][r]), s_acc[1][qt][r]);
                     a = fmaxf(a, __shfl_xor(a, 32));
                     const float m_new = fmaxf(a, m_used[qt]);
-                    const float alpha = __builtin_amdgcn_exp2f(m_used[qt] - m_new);
+                    const float alpha = __builtin_amdgcn_exp2f(EXACTQ ? (m_used[qt] - m_new) * c : m_used[qt] - m_new);
                     m_used[qt] = m_new;
                     l_sum[qt] *= alpha;
 #pragma unroll
@@ -700,8 +715,8 @@ attn_fwd_bf16_d64(FwdParams p) {
                 for (int g = 0; g < 2; ++g)
 #pragma unroll
                     for (int jj = 0; jj < 4; ++jj) {
-                        const float p0 = __builtin_amdgcn_exp2f(S[qt][8 * g + 2 * jj] - sub);
-                        const float p1 = __builtin_amdgcn_exp2f(S[qt][8 * g + 2 * jj + 1] - sub);
+                        const float p0 = __builtin_amdgcn_exp2f(EXACTQ ? (S[qt][8 * g + 2 * jj] - sub) * c : S[qt][8 * g + 2 * jj] - sub);
+                        const float p1 = __builtin_amdgcn_exp2f(EXACTQ ? (S[qt][8 * g + 2 * jj + 1] - sub) * c : S[qt][8 * g + 2 * jj + 1] - sub);
                         const f32x2 pp = {p0, p1};
                         const bf16x2 pb = __builtin_convertvector(pp, bf16x2);
                         l += p0;
@@ -717,8 +732,8 @@ attn_fwd_bf16_d64(FwdParams p) {
                 for (int g = 0; g < 2; ++g)
 #pragma unroll
                     for (int jj = 0; jj < 4; ++jj) {
-                        const float p0 = __builtin_amdgcn_exp2f(S[qt][8 * g + 2 * jj]);
-                        const float p1 = __builtin_amdgcn_exp2f(S[qt][8 * g + 2 * jj + 1]);
+                        const float p0 = __builtin_amdgcn_exp2f(EXACTQ ? S[qt][8 * g + 2 * jj] * c : S[qt][8 * g + 2 * jj]);
+                        const float p1 = __builtin_amdgcn_exp2f(EXACTQ ? S[qt][8 * g + 2 * jj + 1] * c : S[qt][8 * g + 2 * jj + 1]);
                         const f32x2 pp = {p0, p1};
                         const bf16x2 pb = __builtin_convertvector(pp, bf16x2);
                         l += p0;
@@ -738,7 +753,7 @@ attn_fwd_bf16_d64(FwdParams p) {
                     for (int r = 1; r < 16; ++r) a = fmaxf(a, S[qt][r]);
                     a = fmaxf(a, __shfl_xor(a, 32));          // relative to the current reference
                     const float up = fresh ? a : fmaxf(a, 0.f);
-                    const float alpha = fresh ? 0.f : __builtin_amdgcn_exp2f(-up);
+                    const float alpha = fresh ? 0.f : __builtin_amdgcn_exp2f(EXACTQ ? -up * c : -up);
                     m_used[qt] = (fresh ? 0.f : m_used[qt]) + up;
                     l_sum[qt] *= alpha;
 #pragma unroll
@@ -821,6 +836,9 @@ attn_fwd_bf16_d64(FwdParams p) {
         run_rest(t_pipe, t_mid, std::integral_constant<int, 0>{});
         run_rest(t_mid, t_end, std::integral_constant<int, 1>{});
         if (!wave_active) return;
+        if constexpr (EXACTQ)
+#pragma unroll
+            for (int qt = 0; qt < QT; ++qt) m_used[qt] *= c;
         store_rows<QT>(p, wi, row, h, o_acc, l_sum, m_used);
         return;
     }
@@ -900,6 +918,9 @@ attn_fwd_bf16_d64(FwdParams p) {
 #pragma unroll
                 for (int r = 0; r < 16; ++r) o_acc[dt][qt][r] *= vs;
     }
+    if constexpr (EXACTQ)
+#pragma unroll
+        for (int qt = 0; qt < QT; ++qt) m_used[qt] *= c;
     store_rows<QT>(p, wi, row, h, o_acc, l_sum, m_used);
 }
 

@@ -302,6 +302,10 @@ static int fwd_impl(nfd_attn_t* h, const void* q, const void* k, const void* v, 
             hipLaunchKernelGGL((nfd::mfma::attn_fwd_bf16_d64<2, true>), grid, block, 0, st, p);
         else if (kv8)
             hipLaunchKernelGGL((nfd::mfma::attn_fwd_bf16_d64<1, true>), grid, block, 0, st, p);
+        else if (lse && pl.block_m == nfd::mfma::kBM)  // training pair: scores from the queries as given
+            hipLaunchKernelGGL((nfd::mfma::attn_fwd_bf16_d64<2, false, true>), grid, block, 0, st, p);
+        else if (lse)
+            hipLaunchKernelGGL((nfd::mfma::attn_fwd_bf16_d64<1, false, true>), grid, block, 0, st, p);
         else if (pl.block_m == nfd::mfma::kBM)
             hipLaunchKernelGGL((nfd::mfma::attn_fwd_bf16_d64<2, false>), grid, block, 0, st, p);
         else

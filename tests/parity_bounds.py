@@ -23,3 +23,7 @@ def worst_row(got, ref):
     r = row_errors(got, ref)
     i = int(r.argmax())
     return float(r.reshape(-1)[i]), np.unravel_index(i, r.shape)
+
+# Log-sum-exp written by the forward of the training pair (absolute, natural units): fp32 sums of fp32 exponentials
+# of scores accumulated exactly from the bf16 inputs; measured < 1e-5.
+BF16_LSE_ABS = 2e-4

@@ -4,7 +4,7 @@ ragged key blocks, frames that straddle tiles, head counts that do not divide by
 XCDs, spare cache capacity and key splits."""
 import numpy as np
 import pytest
-from parity_bounds import BF16_ROW_REL_L2, worst_row
+from parity_bounds import BF16_LSE_ABS, BF16_ROW_REL_L2, worst_row
 import torch
 
 from oracle import nfd_oracle as orc
@@ -57,7 +57,8 @@ def test_forward_and_backward_on_random_shapes(attn, B, H, T, kvf, qf, F):
     out, lse = attn.forward_lse(qd, kd, vd, T, kv_frames=kvf, q_frames=qf)
     dq, dk, dv = attn.backward(qd, kd, vd, out, gd, lse, T, kv_frames=kvf, q_frames=qf)
     torch.cuda.synchronize()
-    assert torch.equal(out, out_plain)  # writing the log-sum-exp does not change the output
+    # the forward of the training pair forms its scores from the queries as given, the plain forward from queries that
+    # carry the softmax scale (one more bf16 rounding): two results, both checked against the oracle below
     kz, vz = np.nan_to_num(k), np.nan_to_num(v)
     ref = orc.block_causal_attn(q, kz, vz, T, kv_frames=kvf, q_frames=qf)
     rdq, rdk, rdv, rlse = orc.block_causal_attn_bwd(q, kz, vz, g, T, kv_frames=kvf, q_frames=qf)
@@ -71,10 +72,12 @@ def test_forward_and_backward_on_random_shapes(attn, B, H, T, kvf, qf, F):
 
     close(_host(out), ref, "out")
     assert worst_row(_host(out), ref)[0] <= BF16_ROW_REL_L2
+    close(_host(out_plain), ref, "out (plain forward)")
+    assert worst_row(_host(out_plain), ref)[0] <= BF16_ROW_REL_L2
     close(_host(dq), rdq, "dq")
     close(_host(dk)[:, :, :Sk], rdk[:, :, :Sk], "dk")
     close(_host(dv)[:, :, :Sk], rdv[:, :, :Sk], "dv")
-    assert np.abs(lse.cpu().numpy() - rlse).max() <= 2e-4
+    assert np.abs(lse.cpu().numpy() - rlse).max() <= BF16_LSE_ABS
     assert np.all(_host(dk)[:, :, Sk:] == 0) and np.all(_host(dv)[:, :, Sk:] == 0)
 
 

@@ -68,9 +68,9 @@ def test_noalloc_forward_without_splits_and_fp32():
 
 
 def test_noalloc_forward_refuses_what_does_not_fit_and_bad_arguments():
-    # the batched long-context decode needs 40 MB of partials: beyond the 32 MiB array -> refused, nothing launched
-    cfg = wl.CONFIGS["c5b_batch_decode"]
-    B, H, D, T, kvf, qf, F = (cfg[x] for x in ("B", "H", "D", "T", "kv_frames", "q_frames", "F"))
+    # a batched decode of 8 sequences with 768-token frames over 48 frames needs 51 MiB for its partials, more than
+    # the 32 MiB array -> refused, nothing launched
+    B, H, D, T, kvf, qf, F = 8, 16, 64, 768, 48, 1, 48
     assert nb.nfd_attn_plan(nb.NFD_BF16, B, H, F, T, D, kvf, qf)["workspace_bytes"] > 32 << 20
     q = torch.zeros((B, H, qf * T, D), dtype=torch.bfloat16, device="cuda")
     k = torch.zeros((B, H, F * T, D), dtype=torch.bfloat16, device="cuda")
