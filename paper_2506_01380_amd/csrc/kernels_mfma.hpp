@@ -119,10 +119,14 @@ __device__ __forceinline__ bf16x8 widen_e4m3x8(uint32_t w0, uint32_t w1) {
 // (or idle), and the items are dealt out plainly, consecutive ids going to consecutive heads.
 // Order of the items of an XCD (or of the launch):
 //  * by default the heaviest query tiles (latest frames) come first, heads fastest, so the tail
-//    of the launch is made of the lightest tiles;
+//    of the launch is made of the lightest tiles; with more than kHeadGroup heads in the stream they go in
+//    groups of that many, one group after the other: the workgroups resident together then belong to few
+//    heads and share their K/V tiles in L2 (256 heads x 21 tiles: 917 -> 1017 TFLOP/s), while a group
+//    is still large enough to end on light tiles;
 //  * group_q_tiles (key-split launches whose K/V exceed the last-level cache): the query tiles of
 //    one (head, split) are consecutive instead, so they are resident together and their common
 //    K/V range is fetched from HBM once and found in L2 by the others.
+constexpr int kHeadGroup = 8;
 struct WorkItem {
     int bh, q_tile, split;
     bool valid;
@@ -138,8 +142,12 @@ __host__ __device__ __forceinline__ WorkItem work_item_of(unsigned block, int BH
     w.valid = j < hh * per_head;
     int head_local;
     if (!group_q_tiles) {
-        const int item = j / hh;
-        head_local = j % hh;
+        // heads in groups of kHeadGroup: all items of a group before the next group's
+        const int per_group = kHeadGroup * per_head;
+        const int g0 = j / per_group * kHeadGroup, jj = j % per_group;
+        const int gh = max(1, min(kHeadGroup, hh - g0));  // heads of this group (the last one may be smaller; an id past the launch: 1)
+        const int item = jj / gh;
+        head_local = g0 + jj % gh;
         w.q_tile = n_q_tiles - 1 - item / n_splits;
         w.split = item % n_splits;
     } else {
@@ -219,23 +227,31 @@ __device__ __forceinline__ void store_rows(const FwdParams& p, const WorkItem& w
 // queries enter the first product as given, the scores are exact sums of products of the inputs, and the softmax
 // scale is applied to the fp32 scores (one multiply per score); the reference max is then kept in raw score units.
 // Without it the scale is folded into the query fragments (one more bf16 rounding of an input, no multiply).
-template <int QT, bool KV8 = false, bool EXACTQ = false>
-__global__ void __launch_bounds__(kWaves * 64, QT == 2 ? 2 : 3)
-attn_fwd_bf16_d64(FwdParams p) {
-    constexpr int BM = kWaves * 32 * QT;
+template <int QT, bool KV8>
+struct SmemOf {
+    static constexpr bool WIDE = KV8 && QT == 2;   // tiles widened once per workgroup (see SmemRing8Wide)
+    static constexpr bool PIPE = !KV8 && QT == 2;  // software-pipelined tile loop (see the PIPE branch below)
+    typedef typename std::conditional<WIDE, SmemRing8Wide, typename std::conditional<KV8, SmemRing8,
+                     typename std::conditional<PIPE, SmemRingPipe, SmemRing>::type>::type>::type type;
+};
+
+// One work item (head, query tile, key split) from the first load to the final write.  Every wavefront of the
+// workgroup passes the same barriers and returns; the LDS ring may be reused after a workgroup barrier.
+template <int QT, bool KV8, bool EXACTQ>
+__device__ __forceinline__ void attn_fwd_item(const FwdParams& p, const WorkItem& wi, typename SmemOf<QT, KV8>::type& sm) {
     constexpr int PRIO = kMfmaPriority;
-    constexpr bool WIDE = KV8 && QT == 2;  // tiles widened once per workgroup (see SmemRing8Wide)
-    constexpr bool PIPE = !KV8 && QT == 2;  // software-pipelined tile loop (see run_pipe below)
-    __shared__ typename std::conditional<WIDE, SmemRing8Wide, typename std::conditional<KV8, SmemRing8,
-                        typename std::conditional<PIPE, SmemRingPipe, SmemRing>::type>::type>::type sm;
-    const WorkItem wi = decode_work(p);
-    if (!wi.valid) return;  // whole workgroup leaves together
+    constexpr bool WIDE = SmemOf<QT, KV8>::WIDE;
+    constexpr bool PIPE = SmemOf<QT, KV8>::PIPE;
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n = lane & 31, h = lane >> 5;
-    const int r0 = wi.q_tile * BM;
-    const int r_last = min(r0 + BM, p.Sq) - 1;
+    // The 32-row blocks of a head are dealt to the query tiles as evenly as they go: tile i owns blocks_lo blocks,
+    // the first n_hi tiles one more (at most BM / 32), so no tile is mostly padding.
+    const int blk0 = wi.q_tile * p.blocks_lo + min(wi.q_tile, p.n_hi);
+    const int n_blk = p.blocks_lo + (wi.q_tile < p.n_hi ? 1 : 0);
+    const int r0 = 32 * blk0;
+    const int r_last = min(r0 + 32 * n_blk, p.Sq) - 1;
     const int kmax_wg = kmax_of_row(r_last, p.T, p.P);
     const int n_tiles = (kmax_wg + kBN - 1) / kBN;
     const int tiles_per_split = (n_tiles + p.n_splits - 1) / p.n_splits;
@@ -274,12 +290,12 @@ attn_fwd_bf16_d64(FwdParams p) {
     }
 
     // ---- this wavefront's queries -------------------------------------------------------
-    // QT = 2: the wavefront owns the 32-row blocks `wave` and `wave + 4` of the workgroup's 256 rows, not two
+    // QT = 2: the wavefront owns the 32-row blocks `wave` and `wave + 4` of the workgroup's (up to) eight, not two
     // adjacent ones.  Where a frame boundary falls inside the workgroup, the later frame's extra key tiles are
     // then shared by all four wavefronts (each running one block) instead of keeping the last wavefronts busy
-    // with two blocks while the first ones idle.  A ragged last query tile keeps adjacent blocks (2*wave,
-    // 2*wave + 1): there the rows past the end, not a frame boundary, decide which wavefronts have work.
-    const bool full_tile = r0 + BM <= p.Sq;
+    // with two blocks while the first ones idle.  In a tile of fewer than eight blocks the wavefronts without a
+    // block `wave + 4` own block `wave` alone, as their LATER block: the earlier one is dead (no rows, key bound 0),
+    // so every tile runs in the second, one-block loop and nothing is computed for rows that do not exist.
     // The softmax scale (times log2 e, times the K scale of an 8-bit cache) is folded into the query fragments once,
     // rounded to bf16: the score accumulators then hold base-2 exponents directly and the softmax needs no multiply.
     float c = p.scale_log2e;
@@ -289,12 +305,14 @@ attn_fwd_bf16_d64(FwdParams p) {
     bf16x8 qf[QT][4];
 #pragma unroll
     for (int qt = 0; qt < QT; ++qt) {
-        const int b0 = r0 + 32 * (QT == 1 ? wave : full_tile ? wave + kWaves * qt : 2 * wave + qt);
-        row[qt] = b0 + n;
-        const int rc = min(row[qt], p.Sq - 1);  // ragged tail: compute a duplicate, never store it
+        const bool pair = QT == 2 && wave + kWaves < n_blk;   // this wavefront has two blocks
+        const bool dead = QT == 2 && qt == 0 && !pair;         // single block: it is block index 1
+        const int b0 = r0 + 32 * (QT == 2 && qt == 1 && pair ? wave + kWaves : wave);
+        row[qt] = dead ? 0x40000000 : b0 + n;                  // dead rows are never stored
+        const int rc = min(row[qt], p.Sq - 1);  // rows past the end: compute a duplicate, never store it
         kmax_lane[qt] = kmax_of_row(rc, p.T, p.P);
-        kmin_blk[qt] = kmax_of_row(min(b0, p.Sq - 1), p.T, p.P);
-        kmax_blk[qt] = kmax_of_row(min(b0 + 31, p.Sq - 1), p.T, p.P);
+        kmin_blk[qt] = dead ? 0 : kmax_of_row(min(b0, p.Sq - 1), p.T, p.P);
+        kmax_blk[qt] = dead ? 0 : kmax_of_row(min(b0 + 31, p.Sq - 1), p.T, p.P);
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
             // contraction step ks, lane half h: features 16*ks + 8*h ..+7; with the 8-bit cache the features of
@@ -310,7 +328,7 @@ attn_fwd_bf16_d64(FwdParams p) {
         }
     }
     const int kmax_wave = kmax_blk[QT - 1];  // tiles starting at or above are skipped (blocks ascend)
-    const bool wave_active = r0 + 32 * (QT == 1 || full_tile ? wave : 2 * wave) < p.Sq;
+    const bool wave_active = wave < n_blk;
 
     f32x16 o_acc[2][QT];  // [dt][qt]: O^T rows 32*dt.., query block qt
 #pragma unroll
@@ -922,6 +940,15 @@ attn_fwd_bf16_d64(FwdParams p) {
 #pragma unroll
         for (int qt = 0; qt < QT; ++qt) m_used[qt] *= c;
     store_rows<QT>(p, wi, row, h, o_acc, l_sum, m_used);
+}
+
+template <int QT, bool KV8 = false, bool EXACTQ = false>
+__global__ void __launch_bounds__(kWaves * 64, QT == 2 ? 2 : 3)
+attn_fwd_bf16_d64(FwdParams p) {
+    __shared__ typename SmemOf<QT, KV8>::type sm;
+    const WorkItem wi = decode_work(p);
+    if (!wi.valid) return;  // whole workgroup leaves together
+    attn_fwd_item<QT, KV8, EXACTQ>(p, wi, sm);
 }
 
 // Merge the key-split partials of one query row: out = sum_s w_s O_s / sum_s w_s l_s with

@@ -102,13 +102,17 @@ int nfd_attn_plan(nfd_dtype_t dtype, int B, int H, int F, int T, int D, int kv_f
         pl.kernel = 1;
         pl.block_n = nfd::mfma::kBN;
         int64_t visited = 0, max_tiles = 0;
+        // The 32-row blocks of a head are dealt to the query tiles as evenly as they go (see the kernel).
+        const int64_t n_blocks = (Sq + 31) / 32;
         auto tile_counts = [&](int block_m) {
             pl.block_m = block_m;
-            pl.n_q_tiles = (int)((Sq + block_m - 1) / block_m);
+            pl.n_q_tiles = (int)((n_blocks + block_m / 32 - 1) / (block_m / 32));
             visited = 0;
             max_tiles = 0;
+            const int64_t lo = n_blocks / pl.n_q_tiles, hi = n_blocks % pl.n_q_tiles;
             for (int qt = 0; qt < pl.n_q_tiles; ++qt) {
-                const int64_t r_last = std::min<int64_t>((int64_t)(qt + 1) * block_m, Sq) - 1;
+                const int64_t blk_end = (int64_t)(qt + 1) * lo + std::min<int64_t>(qt + 1, hi);
+                const int64_t r_last = std::min<int64_t>(32 * blk_end, Sq) - 1;
                 const int64_t nt = (kmax_rows(r_last, T, P) + pl.block_n - 1) / pl.block_n;
                 visited += nt;
                 max_tiles = std::max(max_tiles, nt);
@@ -271,6 +275,11 @@ static int fwd_impl(nfd_attn_t* h, const void* q, const void* k, const void* v, 
     p.P = kv_frames - q_frames;
     p.D = D;
     p.n_q_tiles = pl.n_q_tiles;
+    {
+        const int n_blocks = (p.Sq + 31) / 32;
+        p.blocks_lo = n_blocks / pl.n_q_tiles;
+        p.n_hi = n_blocks % pl.n_q_tiles;
+    }
     p.n_splits = pl.n_splits;
     // K and V of all heads against the 256 MB last-level cache (with room for Q, O and partials)
     p.group_q_tiles = pl.n_splits > 1 && (double)p.BH * p.Sk * nfd::mfma::kD * 2.0 * (kv8 ? 1.0 : 2.0) > 192e6;

@@ -40,6 +40,8 @@ struct FwdParams {
     int P;              // kv_frames - q_frames
     int D;
     int n_q_tiles;      // query tiles per head
+    int blocks_lo;      // 32-row blocks per query tile; the first n_hi tiles own one more
+    int n_hi;
     int n_splits;       // key splits per query tile
     int group_q_tiles;  // split launches: 1 = query tiles of one (head, split) get adjacent workgroup ids
     float scale_log2e;  // softmax scale * log2(e)

@@ -102,6 +102,12 @@ _FIXED_MANY_HEADS = [
     (4, 16, 17, 40, 40, 41),     # many boundaries inside one workgroup, ragged last tile
     (4, 16, 336, 4, 4, 4),       # the paper's frame size: one boundary in three of four workgroups
     (8, 8, 256, 3, 3, 3),        # frames = workgroups: no boundary inside any
+    # query tiles of fewer than eight 32-row blocks (the blocks of a head are dealt evenly): wavefronts with one block
+    (8, 8, 40, 5, 5, 5),         # 200 rows: one tile of 7 blocks, the last block 8 rows
+    (8, 8, 36, 5, 5, 5),         # 180 rows: 6 blocks
+    (8, 8, 30, 6, 5, 6),         # 150 rows: 5 blocks, cached form
+    (4, 16, 52, 9, 8, 9),        # 416 rows: two tiles, 7 + 6 blocks
+    (4, 16, 336, 6, 4, 6),       # four speculative frames of the paper's size: six tiles of 7 blocks
 ]
 
 

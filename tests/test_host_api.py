@@ -112,7 +112,8 @@ def test_plan_refuses_a_launch_beyond_the_grid_limit():
 
 
 @pytest.mark.parametrize("BH,nq,ns", [(16, 2, 16), (16, 6, 5), (128, 3, 4), (5, 3, 7), (9, 4, 1), (64, 21, 1), (3, 1, 2),
-                                      (1, 1, 1), (17, 2, 3), (12, 3, 16), (24, 21, 1), (8, 1, 1)])
+                                      (1, 1, 1), (17, 2, 3), (12, 3, 16), (24, 21, 1), (8, 1, 1), (256, 21, 1), (136, 2, 1),
+                                      (20, 3, 1), (72, 5, 2)])
 @pytest.mark.parametrize("group", [0, 1])
 def test_every_work_item_is_dealt_exactly_once(BH, nq, ns, group):
     """The workgroup -> (head, query tile, split) map of the forward launch is a bijection onto all items;
@@ -131,6 +132,12 @@ def test_every_work_item_is_dealt_exactly_once(BH, nq, ns, group):
         order = [nb.nfd_attn_work_item(BH, nq, ns, 0, b)[1] for b in range(n)]
         first_of = {q: order.index(q) for q in range(nq)}
         assert all(first_of[q + 1] <= first_of[q] for q in range(nq - 1))
+        # heads go in groups of 8 per id stream (one stream per XCD when heads are pinned, else one in all): every
+        # item of a group is dealt before the next group starts
+        stream = (lambda bh: bh // 8) if BH % 8 == 0 else (lambda bh: bh)
+        for x in range(8 if BH % 8 == 0 else 1):
+            groups = [stream(nb.nfd_attn_work_item(BH, nq, ns, 0, b)[0]) // 8 for b in range(n) if BH % 8 != 0 or b % 8 == x]
+            assert groups == sorted(groups)
 
 
 def test_fp8_cache_bytes_rounds_the_key_count_to_whole_tiles():
