@@ -511,7 +511,12 @@ __device__ __forceinline__ void attn_fwd_item(const FwdParams& p, const WorkItem
             // this point of the next tile: when the two wavefronts of a SIMD are in different
             // stages, the one feeding the matrix pipe (one issue slot per 32-cycle instruction) is
             // never kept waiting by the other one's stream of vector instructions.
-            __builtin_amdgcn_s_setprio(PRIO);
+            // Key-split launches (all workgroups resident at once, equal chains): a workgroup in the first half of its
+            // chain runs one level higher.  Of the workgroups that share a CU the instruction arbiter otherwise serves the
+            // oldest first, which then finishes far ahead and leaves the youngest to run alone at the end.
+            const bool early = !PIPE && p.n_splits > 1 && (t - t_begin) * 2 < t_end - t_begin;
+            if (early) __builtin_amdgcn_s_setprio(PRIO + 1);
+            else __builtin_amdgcn_s_setprio(PRIO);
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb) {
 #pragma unroll
@@ -525,7 +530,8 @@ __device__ __forceinline__ void attn_fwd_item(const FwdParams& p, const WorkItem
                         s_acc[kb][qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kb][ks], qf[qt][ks], s_acc[kb][qt], 0, 0, 0);
             }
             __builtin_amdgcn_sched_barrier(0);
-            __builtin_amdgcn_s_setprio(0);
+            if (early) __builtin_amdgcn_s_setprio(1);
+            else __builtin_amdgcn_s_setprio(0);
             bf16x8 vf[2][2][2];  // [kb][g][dt]
             auto read_v_frags = [&]() {
 #pragma unroll
@@ -636,7 +642,8 @@ __device__ __forceinline__ void attn_fwd_item(const FwdParams& p, const WorkItem
             for (int qt = QA; qt < QT; ++qt) l_sum[qt] += l_tile[qt];
             // ---- O^T += V^T . P^T -----------------------------------------------------------------
             __builtin_amdgcn_sched_barrier(0);
-            __builtin_amdgcn_s_setprio(PRIO);
+            if (early) __builtin_amdgcn_s_setprio(PRIO + 1);
+            else __builtin_amdgcn_s_setprio(PRIO);
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
@@ -675,6 +682,18 @@ __device__ __forceinline__ void attn_fwd_item(const FwdParams& p, const WorkItem
             __builtin_amdgcn_s_barrier();
             __builtin_amdgcn_sched_barrier(0);
             if (t + 3 < t_end) load_tile(t + 3, (t + 3 - t_begin) & 3);
+            // Key-split launches: the wave priority falls with the quarter of the chain the workgroup is in, so that of
+            // two workgroups sharing a CU the one that lags is served first and both finish together (the arbiter
+            // otherwise prefers the older one throughout: 52 against 70 us at four speculative frames).  Training
+            // launches keep one level: there a CU's workgroups differ in length and start time anyway, and changing
+            // levels costs 1-2 %.
+            if (p.n_splits > 1) {
+                const int done4 = (t - t_begin) * 4, len = t_end - t_begin;
+                if (done4 < len) __builtin_amdgcn_s_setprio(3);
+                else if (done4 < 2 * len) __builtin_amdgcn_s_setprio(2);
+                else if (done4 < 3 * len) __builtin_amdgcn_s_setprio(1);
+                else __builtin_amdgcn_s_setprio(0);
+            }
         };
         __builtin_amdgcn_s_barrier();  // "Bar(t_begin - 1)": the first tiles have landed for all (own loads: wait above)
 
