@@ -271,7 +271,9 @@ int nfd_attn_check_args(nfd_dtype_t dtype, int B, int H, int F, int T, int D, in
  * future frames IS the ~50 % saving the paper states). */
 typedef struct nfd_attn_plan {
     int kernel;          /* 0 = general (fp32 / any D), 1 = bf16 matrix-core D=64 */
-    int block_m;         /* query rows per workgroup */
+    int block_m;         /* query rows per workgroup, at most: the 32-row blocks of a head are dealt evenly to its
+                            n_q_tiles tiles (tile i owns floor(blocks / n_q_tiles) blocks, the first blocks mod n_q_tiles
+                            tiles one more) */
     int block_n;         /* keys per inner tile */
     int n_q_tiles;       /* query tiles per (b, h) */
     int n_splits;        /* key splits per query tile (1 = no combine pass) */
