@@ -1,8 +1,9 @@
 // bf16 matrix-core forward kernel for head width 64 (gfx950 / CDNA4).
 //
-// Flash-style online softmax.  A workgroup of 4 wavefronts owns 256 consecutive query rows of
-// one (batch, head); each wavefront owns 64 of them as two 32-wide column blocks (blocks w and
-// w + 4 of the workgroup's eight) of the TRANSPOSED score matrix:
+// Flash-style online softmax.  A workgroup of 4 wavefronts owns up to 256 consecutive query rows of
+// one (batch, head) - the 32-row blocks of a head are dealt evenly to its query tiles -; each wavefront
+// owns 64 of them as two 32-wide column blocks (blocks w and w + 4 of the workgroup's eight; a single
+// block where the tile has fewer) of the TRANSPOSED score matrix:
 //
 //   S^T[key, query] = K_tile[key, :] . Q^T[:, query]       v_mfma_f32_32x32x16_bf16, A = K (LDS), B = Q^T (registers)
 //   O^T[d,   query] += V_tile^T[d, key] . P^T[key, query]  A = V^T (LDS, transposing read), B = P^T (registers)
@@ -14,8 +15,8 @@
 //
 // K and V tiles (64 keys) never pass through registers either: every wavefront issues 16-byte
 // global loads that land straight in LDS (one wave instruction = 1 KB = eight 128-byte tile
-// rows), two tiles ahead of their use, into a ring of three tile slots, with one bare barrier
-// per tile.  A wave's 1 KB is contiguous in LDS, so rows cannot be padded; bank conflicts are
+// rows), two tiles ahead of their use, into a ring of three tile slots (three ahead, four slots in the
+// pipelined 64-row shape), with one bare barrier per tile.  A wave's 1 KB is contiguous in LDS, so rows cannot be padded; bank conflicts are
 // avoided with an XOR swizzle instead: the 16-byte chunk c of tile row r is stored at chunk
 // position c ^ f(r).  The swizzle costs nothing on the way in (each lane simply fetches the
 // chunk that belongs at its position) and one precomputed per-lane offset on the way out.
@@ -23,7 +24,10 @@
 // Softmax is optimistic: P is formed against the reference max of earlier tiles without
 // looking at this tile's max; only if a lane's tile sum reaches kOptimisticLimit (which also
 // catches inf, i.e. the first tile of a row) the tile is redone with its exact max and the
-// accumulators are rescaled.
+// accumulators are rescaled.  The softmax scale lives in the query fragments (rounded to bf16), so the
+// score accumulators hold base-2 exponents; in the pipelined loop the reference enters the first product
+// as its C operand and P = exp2(accumulator).  The forward of the training pair (EXACTQ) keeps the
+// queries as given and scales the fp32 scores instead.
 //
 // Mask (Sec. 3.1): row i sees keys j < kmax(i) = (P + i/T + 1) * T.  Key tiles entirely
 // below every row's bound run with no mask arithmetic; tiles at or beyond the largest
