@@ -343,6 +343,12 @@ int nfd_block_causal_attn_fwd_fp8kv(nfd_attn_t* h, const void* q, const void* k8
 int nfd_attn_work_item(int BH, int n_q_tiles, int n_splits, int group_q_tiles, unsigned block, int* bh, int* q_tile,
                        int* split);
 
+/* Query rows [first_row, first_row + n_rows) of query tile q_tile when a head's `rows` query rows are cut into
+ * n_q_tiles tiles (the plan's count) for the matrix-core forward: the same function the kernel evaluates.  The 32-row
+ * blocks are dealt evenly (tile sizes differ by at most 32 rows); the tiles are disjoint and cover all rows.
+ * Errors: NFD_ERR_NULL, NFD_ERR_SHAPE, NFD_ERR_UNSUPPORTED (rows beyond the 2^30 of the attention calls). */
+int nfd_attn_q_tile_rows(int rows, int n_q_tiles, int q_tile, int* first_row, int* n_rows);
+
 /* Visible (query, key) pairs per (b, h): T^2 (q_frames P + q_frames (q_frames + 1) / 2). */
 int64_t nfd_attn_visible_pairs(int T, int kv_frames, int q_frames);
 

@@ -28,6 +28,7 @@ EXPORTS = (
     "nfd_block_causal_attn_fwd_lse", "nfd_block_causal_attn_bwd",
     "nfd_kvcache_shift", "nfd_spec_init", "nfd_spec_next", "nfd_spec_accept", "nfd_attn_work_item",
     "nfd_block_causal_attn_fwd_noalloc", "nfd_kvcache_append_attn_fwd",
+    "nfd_attn_q_tile_rows",
     "nfd_fp8_cache_bytes", "nfd_kvcache_append_fp8", "nfd_block_causal_attn_fwd_fp8kv", "nfd_kvcache_shift_fp8", "nfd_rope_kvcache_append_fp8",
 )
 
@@ -112,6 +113,8 @@ def lib():
         L.nfd_attn_plan.restype = ci
         L.nfd_attn_work_item.argtypes = [ci] * 4 + [ctypes.c_uint] + [ctypes.POINTER(ci)] * 3
         L.nfd_attn_work_item.restype = ci
+        L.nfd_attn_q_tile_rows.argtypes = [ci] * 3 + [ctypes.POINTER(ci)] * 2
+        L.nfd_attn_q_tile_rows.restype = ci
         L.nfd_fp8_cache_bytes.argtypes = [ci] * 5 + [ctypes.POINTER(ctypes.c_size_t)]
         L.nfd_fp8_cache_bytes.restype = ci
         L.nfd_kvcache_append_fp8.argtypes = [vp] * 7 + [ci] * 7 + [vp]
@@ -297,6 +300,13 @@ def nfd_attn_work_item(BH, n_q_tiles, n_splits, group_q_tiles, block):
     rc = lib().nfd_attn_work_item(BH, n_q_tiles, n_splits, int(group_q_tiles), block, ctypes.byref(bh), ctypes.byref(qt),
                                   ctypes.byref(sp))
     return (bh.value, qt.value, sp.value) if rc == NFD_OK else None
+
+
+def nfd_attn_q_tile_rows(rows, n_q_tiles, q_tile):
+    """(first_row, n_rows) of a query tile of the matrix-core forward, or None for arguments out of range."""
+    r0, n = ctypes.c_int(), ctypes.c_int()
+    rc = lib().nfd_attn_q_tile_rows(rows, n_q_tiles, q_tile, ctypes.byref(r0), ctypes.byref(n))
+    return (r0.value, n.value) if rc == NFD_OK else None
 
 
 def nfd_attn_visible_pairs(T, kv_frames, q_frames):

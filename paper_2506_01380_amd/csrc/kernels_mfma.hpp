@@ -131,6 +131,15 @@ __device__ __forceinline__ bf16x8 widen_e4m3x8(uint32_t w0, uint32_t w1) {
 //    one (head, split) are consecutive instead, so they are resident together and their common
 //    K/V range is fetched from HBM once and found in L2 by the others.
 constexpr int kHeadGroup = 8;
+
+// The 32-row blocks of a head are dealt to its query tiles as evenly as they go: tile i owns blocks_lo blocks, the
+// first n_hi tiles one more, so no tile is mostly padding.  (blocks_lo = n_blocks / n_q_tiles, n_hi = n_blocks mod
+// n_q_tiles, n_blocks = ceil(rows / 32).)
+__host__ __device__ __forceinline__ void q_tile_blocks(int q_tile, int blocks_lo, int n_hi, int* first_block, int* n_blocks) {
+    *first_block = q_tile * blocks_lo + (q_tile < n_hi ? q_tile : n_hi);
+    *n_blocks = blocks_lo + (q_tile < n_hi ? 1 : 0);
+}
+
 struct WorkItem {
     int bh, q_tile, split;
     bool valid;
@@ -250,10 +259,8 @@ __device__ __forceinline__ void attn_fwd_item(const FwdParams& p, const WorkItem
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n = lane & 31, h = lane >> 5;
-    // The 32-row blocks of a head are dealt to the query tiles as evenly as they go: tile i owns blocks_lo blocks,
-    // the first n_hi tiles one more (at most BM / 32), so no tile is mostly padding.
-    const int blk0 = wi.q_tile * p.blocks_lo + min(wi.q_tile, p.n_hi);
-    const int n_blk = p.blocks_lo + (wi.q_tile < p.n_hi ? 1 : 0);
+    int blk0, n_blk;  // this tile's 32-row blocks (at most eight)
+    q_tile_blocks(wi.q_tile, p.blocks_lo, p.n_hi, &blk0, &n_blk);
     const int r0 = 32 * blk0;
     const int r_last = min(r0 + 32 * n_blk, p.Sq) - 1;
     const int kmax_wg = kmax_of_row(r_last, p.T, p.P);

@@ -109,10 +109,11 @@ int nfd_attn_plan(nfd_dtype_t dtype, int B, int H, int F, int T, int D, int kv_f
             pl.n_q_tiles = (int)((n_blocks + block_m / 32 - 1) / (block_m / 32));
             visited = 0;
             max_tiles = 0;
-            const int64_t lo = n_blocks / pl.n_q_tiles, hi = n_blocks % pl.n_q_tiles;
+            const int lo = (int)(n_blocks / pl.n_q_tiles), hi = (int)(n_blocks % pl.n_q_tiles);
             for (int qt = 0; qt < pl.n_q_tiles; ++qt) {
-                const int64_t blk_end = (int64_t)(qt + 1) * lo + std::min<int64_t>(qt + 1, hi);
-                const int64_t r_last = std::min<int64_t>(32 * blk_end, Sq) - 1;
+                int b0, nb;
+                nfd::mfma::q_tile_blocks(qt, lo, hi, &b0, &nb);
+                const int64_t r_last = std::min<int64_t>(32 * (int64_t)(b0 + nb), Sq) - 1;
                 const int64_t nt = (kmax_rows(r_last, T, P) + pl.block_n - 1) / pl.block_n;
                 visited += nt;
                 max_tiles = std::max(max_tiles, nt);
@@ -172,6 +173,18 @@ int nfd_attn_plan(nfd_dtype_t dtype, int B, int H, int F, int T, int D, int kv_f
         pl.workspace_bytes = 0;
     }
     *plan = pl;
+    return NFD_OK;
+}
+
+int nfd_attn_q_tile_rows(int rows, int n_q_tiles, int q_tile, int* first_row, int* n_rows) {
+    if (!first_row || !n_rows) return NFD_ERR_NULL;
+    if (rows < 1 || n_q_tiles < 1 || q_tile < 0 || q_tile >= n_q_tiles) return NFD_ERR_SHAPE;
+    if (rows > 1 << 30) return NFD_ERR_UNSUPPORTED;  // the row limit of the attention calls (32-bit indexing)
+    const int n_blocks = (rows + 31) / 32;
+    int b0, nb;
+    nfd::mfma::q_tile_blocks(q_tile, n_blocks / n_q_tiles, n_blocks % n_q_tiles, &b0, &nb);
+    *first_row = std::min(32 * b0, rows);  // more tiles than blocks (never planned): the surplus tiles are empty
+    *n_rows = std::min(32 * (b0 + nb), rows) - *first_row;
     return NFD_OK;
 }
 

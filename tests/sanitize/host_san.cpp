@@ -53,6 +53,21 @@ static void plans() {
                                 std::free(pl);
                             }
     CHECK(n_ok > 100);
+    int r0, nr;
+    CHECK(nfd_attn_q_tile_rows(INT_MAX, 3, 2, &r0, &nr) == NFD_ERR_UNSUPPORTED);
+    for (int rows : {1, 31, 32, 33, 336, 1344, 5376, 36864, 1 << 30})
+        for (int nq : {1, 2, 3, 6, 21, 144, 1 << 20}) {
+            long covered = 0;
+            for (int qt = 0; qt < nq && qt < 200; ++qt) {
+                int r0 = -1, n = -1;
+                const int rc = nfd_attn_q_tile_rows(rows, nq, qt, &r0, &n);
+                CHECK(rc == NFD_OK && r0 >= 0 && n >= 0 && (long)r0 + n <= rows);
+                CHECK(r0 == covered || n == 0);
+                covered += n;
+            }
+            if (nq <= 200) CHECK(covered == rows);
+        }
+    CHECK(nfd_attn_q_tile_rows(10, 1, 1, &r0, &nr) == NFD_ERR_SHAPE && nfd_attn_q_tile_rows(10, 1, 0, nullptr, &nr) == NFD_ERR_NULL);
     CHECK(nfd_attn_plan(NFD_BF16, 1, 1, 1, 1, 64, 1, 1, 256, 0, nullptr) == NFD_ERR_NULL);
     int a, b;
     CHECK(nfd_attn_work_item(1, 1, 1, 0, 0, &a, &b, nullptr) == NFD_ERR_NULL);

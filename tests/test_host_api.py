@@ -149,3 +149,28 @@ def test_fp8_cache_bytes_rounds_the_key_count_to_whole_tiles():
     assert nb.lib().nfd_fp8_cache_bytes(1, 1, 1, 16, 128, ctypes.byref(n)) == nb.NFD_ERR_UNSUPPORTED
     assert nb.lib().nfd_fp8_cache_bytes(0, 1, 1, 16, 64, ctypes.byref(n)) == nb.NFD_ERR_SHAPE
     assert nb.lib().nfd_fp8_cache_bytes(1, 1, 1, 16, 64, None) == nb.NFD_ERR_NULL
+
+
+@pytest.mark.parametrize("T,qf,B,H", [(336, 4, 1, 16), (336, 2, 1, 16), (336, 1, 1, 16), (336, 16, 4, 16), (576, 1, 8, 16), (7, 5, 1, 2),
+                                      (1, 300, 8, 8), (50, 9, 2, 3), (100, 3, 4, 16), (33, 5, 8, 8), (130, 7, 9, 9)])
+def test_query_tiles_cover_every_row_once_and_evenly(T, qf, B, H):
+    """The rows of a head are cut into the plan's query tiles without gap or overlap; the 32-row blocks are dealt
+    evenly, so no tile is larger than block_m and tile sizes differ by at most one block."""
+    pl = nb.nfd_attn_plan(nb.NFD_BF16, B, H, qf + 3, T, 64, qf + 3, qf)
+    rows, nq = qf * T, pl["n_q_tiles"]
+    nxt, sizes = 0, []
+    for qt in range(nq):
+        r0, n = nb.nfd_attn_q_tile_rows(rows, nq, qt)
+        assert r0 == nxt and 1 <= n <= pl["block_m"] and r0 % 32 == 0
+        nxt += n
+        sizes.append(n)
+    assert nxt == rows
+    assert max(sizes[:-1] + [sizes[-1]]) - min(sizes[:-1] or sizes) <= 32   # the last tile may also lose a partial block
+    assert nb.nfd_attn_q_tile_rows(rows, nq, nq) is None and nb.nfd_attn_q_tile_rows(0, nq, 0) is None
+    # the plan's count of visited key tiles follows from these tiles: the last row of a tile sets its chain
+    visited = 0
+    P = 3
+    for qt in range(nq):
+        r0, n = nb.nfd_attn_q_tile_rows(rows, nq, qt)
+        visited += -(-((P + (r0 + n - 1) // T + 1) * T) // 64)
+    assert pl["key_tiles_visited"] == visited * B * H
