@@ -1,4 +1,6 @@
-// bf16 matrix-core forward kernel for head width 64 (gfx950 / CDNA4).
+// bf16 matrix-core forward kernels for head width 64 (gfx950 / CDNA4): what all shapes share, and the shapes built
+// on the 32x32x16 matrix instruction - the 128-row latency shape, and both shapes over the 8-bit cache.  The 256-row
+// throughput shape over a bf16 cache is in kernels_mfma16.hpp (same structure, 16x16x32 instruction).
 //
 // Flash-style online softmax.  A workgroup of 4 wavefronts owns up to 256 consecutive query rows of
 // one (batch, head) - the 32-row blocks of a head are dealt evenly to its query tiles -; each wavefront
@@ -16,8 +18,8 @@
 // K and V tiles (64 keys) never pass through registers either: every wavefront issues 16-byte
 // global loads that land straight in LDS (one wave instruction = 1 KB = eight 128-byte tile
 // rows), two tiles ahead of their use, into a ring of three tile slots (three ahead, four slots in the
-// pipelined 64-row shape), with one bare barrier per tile.  A wave's 1 KB is contiguous in LDS, so rows cannot be padded; bank conflicts are
-// avoided with an XOR swizzle instead: the 16-byte chunk c of tile row r is stored at chunk
+// pipelined 256-row shape), with one bare barrier per tile.  A wave's 1 KB is contiguous in LDS, so rows
+// cannot be padded; bank conflicts are avoided with an XOR swizzle instead: the 16-byte chunk c of tile row r is stored at chunk
 // position c ^ f(r).  The swizzle costs nothing on the way in (each lane simply fetches the
 // chunk that belongs at its position) and one precomputed per-lane offset on the way out.
 //
@@ -25,8 +27,7 @@
 // looking at this tile's max; only if a lane's tile sum reaches kOptimisticLimit (which also
 // catches inf, i.e. the first tile of a row) the tile is redone with its exact max and the
 // accumulators are rescaled.  The softmax scale lives in the query fragments (rounded to bf16), so the
-// score accumulators hold base-2 exponents; in the pipelined loop the reference enters the first product
-// as its C operand and P = exp2(accumulator).  The forward of the training pair (EXACTQ) keeps the
+// score accumulators hold base-2 exponents.  The forward of the training pair (EXACTQ) keeps the
 // queries as given and scales the fp32 scores instead.
 //
 // Mask (Sec. 3.1): row i sees keys j < kmax(i) = (P + i/T + 1) * T.  Key tiles entirely
@@ -76,8 +77,9 @@ struct __attribute__((aligned(16))) SmemRing {
     __bf16 k[kRingSlots][kTileElems];
     __bf16 v[kRingSlots][kTileElems];
 };
-// The pipelined 64-row shape keeps the V tile of the previous key tile alive while it works on the K tile of the
-// next one, so its ring is one slot deeper for the same prefetch distance (64 KB, two workgroups per CU).
+// The pipelined 256-row shape (kernels_mfma16.hpp) keeps the V tile of the previous key tile alive while it works on
+// the K tile of the next one, so its ring is one slot deeper for the same prefetch distance (64 KB, two workgroups
+// per CU).
 constexpr int kPipeSlots = 4;
 struct __attribute__((aligned(16))) SmemRingPipe {
     __bf16 k[kPipeSlots][kTileElems];
@@ -242,10 +244,9 @@ __device__ __forceinline__ void store_rows(const FwdParams& p, const WorkItem& w
 // Without it the scale is folded into the query fragments (one more bf16 rounding of an input, no multiply).
 template <int QT, bool KV8>
 struct SmemOf {
+    static_assert(QT == 1 || KV8, "the 256-row shape over a bf16 cache is attn_fwd_item16");
     static constexpr bool WIDE = KV8 && QT == 2;   // tiles widened once per workgroup (see SmemRing8Wide)
-    static constexpr bool PIPE = !KV8 && QT == 2;  // software-pipelined tile loop (see the PIPE branch below)
-    typedef typename std::conditional<WIDE, SmemRing8Wide, typename std::conditional<KV8, SmemRing8,
-                     typename std::conditional<PIPE, SmemRingPipe, SmemRing>::type>::type>::type type;
+    typedef typename std::conditional<WIDE, SmemRing8Wide, typename std::conditional<KV8, SmemRing8, SmemRing>::type>::type type;
 };
 
 // One work item (head, query tile, key split) from the first load to the final write.  Every wavefront of the
@@ -254,7 +255,6 @@ template <int QT, bool KV8, bool EXACTQ>
 __device__ __forceinline__ void attn_fwd_item(const FwdParams& p, const WorkItem& wi, typename SmemOf<QT, KV8>::type& sm) {
     constexpr int PRIO = kMfmaPriority;
     constexpr bool WIDE = SmemOf<QT, KV8>::WIDE;
-    constexpr bool PIPE = SmemOf<QT, KV8>::PIPE;
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -467,7 +467,7 @@ __device__ __forceinline__ void attn_fwd_item(const FwdParams& p, const WorkItem
 
     if (t_begin < t_end) load_tile(t_begin, 0);
     if (t_begin + 1 < t_end) load_tile(t_begin + 1, 1);
-    if constexpr (WIDE || PIPE)
+    if constexpr (WIDE)
         if (t_begin + 2 < t_end) load_tile(t_begin + 2, 2);
     // The Q fragments are complete from here on and the compiler knows it: no later guard on them
     // can drain the tile prefetch.  (This also lands tiles 0 and 1, once per workgroup.)
@@ -525,7 +525,7 @@ __device__ __forceinline__ void attn_fwd_item(const FwdParams& p, const WorkItem
             // Key-split launches (all workgroups resident at once, equal chains): a workgroup in the first half of its
             // chain runs one level higher.  Of the workgroups that share a CU the instruction arbiter otherwise serves the
             // oldest first, which then finishes far ahead and leaves the youngest to run alone at the end.
-            const bool early = !PIPE && p.n_splits > 1 && (t - t_begin) * 2 < t_end - t_begin;
+            const bool early = p.n_splits > 1 && (t - t_begin) * 2 < t_end - t_begin;
             if (early) __builtin_amdgcn_s_setprio(PRIO + 1);
             else __builtin_amdgcn_s_setprio(PRIO);
 #pragma unroll
@@ -668,228 +668,6 @@ __device__ __forceinline__ void attn_fwd_item(const FwdParams& p, const WorkItem
         }
     };
 
-    if constexpr (PIPE) {
-        // ---- software-pipelined tile loop (64-row wavefronts over a bf16 cache) -------------------------------
-        // A key tile is four units (kb, qt): 32 keys x one 32-row query block.  Unit u = 2*kb + qt needs
-        //   QK(u): 4 MFMA  S[qt] = K[kb] . Q[qt]^T - reference      (the reference enters as the MFMA's C operand)
-        //   SM(u): 16 exp2, 16 adds, 8 packed conversions per lane  P[qt] = exp2(S[qt])
-        //   PV(u): 4 MFMA  O[qt] += V[kb]^T . P[qt]^T
-        // and step u of the loop issues QK(u+1), SM(u) and PV(u-1) together: the two MFMA groups belong to the other
-        // query block, so nothing in a step depends on anything else in it and the eight MFMAs interleave with the
-        // vector instructions of the softmax inside one wavefront.  Consecutive units alternate between the blocks.
-        // Only tiles that both blocks see entirely (no mask) run here; the few tiles at the frame bounds and the
-        // tiles only the later block sees run through tile_body afterwards.
-        //
-        // Ring contract (both loops of this shape): Bar(t), one barrier per tile t.  A wavefront arrives when its own
-        // loads of tile t+1 have landed and it no longer reads tile t-1; after Bar(t) tile t+1 is visible to all and
-        // every wavefront requests tile t+3 into the slot of tile t-1.  The pipelined loop passes Bar(t) after its
-        // first step of tile t (which still reads V of tile t-1), tile_body's loop at the top of tile t.
-        const int t_mid = wave_active ? max(t_begin, min(t_end, (kmax_blk[0] + kBN - 1) / kBN)) : t_begin;
-        int t_pipe = wave_active ? max(t_begin, min(t_mid, kmin_blk[0] / kBN)) : t_begin;
-        if (t_pipe - t_begin < 2) t_pipe = t_begin;
-        auto bar = [&](int t) {
-            if (t + 2 < t_end) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
-            else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-            __builtin_amdgcn_s_barrier();
-            __builtin_amdgcn_sched_barrier(0);
-            if (t + 3 < t_end) load_tile(t + 3, (t + 3 - t_begin) & 3);
-            // Key-split launches: the wave priority falls with the quarter of the chain the workgroup is in, so that of
-            // two workgroups sharing a CU the one that lags is served first and both finish together (the arbiter
-            // otherwise prefers the older one throughout: 52 against 70 us at four speculative frames).  Training
-            // launches keep one level: there a CU's workgroups differ in length and start time anyway, and changing
-            // levels costs 1-2 %.
-            if (p.n_splits > 1) {
-                const int done4 = (t - t_begin) * 4, len = t_end - t_begin;
-                if (done4 < len) __builtin_amdgcn_s_setprio(3);
-                else if (done4 < 2 * len) __builtin_amdgcn_s_setprio(2);
-                else if (done4 < 3 * len) __builtin_amdgcn_s_setprio(1);
-                else __builtin_amdgcn_s_setprio(0);
-            }
-        };
-        __builtin_amdgcn_s_barrier();  // "Bar(t_begin - 1)": the first tiles have landed for all (own loads: wait above)
-
-        if (t_pipe > t_begin) {
-            f32x16 S[2], minit[2];
-            bf16x8 P[2][2];       // [qt][g]
-            bf16x8 kf[2][4];      // [kb][ks]
-            bf16x8 vf[2][2][2];   // [kb][g][dt]
-#pragma unroll
-            for (int qt = 0; qt < 2; ++qt) {
-#pragma unroll
-                for (int r = 0; r < 16; ++r) minit[qt][r] = 0.f;  // reference 0 until the first unit has set one
-#pragma unroll
-                for (int g = 0; g < 2; ++g)
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) P[qt][g][e] = (__bf16)0.f;
-            }
-#pragma unroll
-            for (int g = 0; g < 2; ++g)
-#pragma unroll
-                for (int dt = 0; dt < 2; ++dt)
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) vf[1][g][dt][e] = (__bf16)0.f;  // the first step's PV adds 0 . 0
-            auto read_k = [&](int t, int kb) {
-                const __bf16* ks_ = sm.k[(t - t_begin) & 3] + 32 * kb * kD;
-#pragma unroll
-                for (int ks = 0; ks < 4; ++ks) kf[kb][ks] = lds_read_b128(ks_ + k_off[ks]);
-            };
-            auto read_v = [&](int t, int kb) {
-                const __bf16* vs_ = sm.v[(t - t_begin) & 3] + 32 * kb * kD;
-#pragma unroll
-                for (int g = 0; g < 2; ++g)
-#pragma unroll
-                    for (int dt = 0; dt < 2; ++dt) {
-                        const s16x4 lo = lds_read_tr(vs_ + 16 * g * kD + v_off[dt][0]);
-                        const s16x4 hi = lds_read_tr(vs_ + 16 * g * kD + v_off[dt][1]);
-                        vf[kb][g][dt] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
-                    }
-            };
-            auto qk = [&](int kb, int qt) {
-                S[qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kb][0], qf[qt][0], minit[qt], 0, 0, 0);
-#pragma unroll
-                for (int ks = 1; ks < 4; ++ks) S[qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kb][ks], qf[qt][ks], S[qt], 0, 0, 0);
-            };
-            auto pv = [&](int kb, int qt) {
-#pragma unroll
-                for (int g = 0; g < 2; ++g)
-#pragma unroll
-                    for (int dt = 0; dt < 2; ++dt)
-                        o_acc[dt][qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[kb][g][dt], P[qt][g], o_acc[dt][qt], 0, 0, 0);
-            };
-            // softmax of one unit against the block's reference (already subtracted by the MFMA); returns the lane's sum
-            auto sm_unit = [&](int qt, float sub) {
-                float l = 0.f, l2 = 0.f;
-#pragma unroll
-                for (int g = 0; g < 2; ++g)
-#pragma unroll
-                    for (int jj = 0; jj < 4; ++jj) {
-                        const float p0 = __builtin_amdgcn_exp2f(EXACTQ ? (S[qt][8 * g + 2 * jj] - sub) * c : S[qt][8 * g + 2 * jj] - sub);
-                        const float p1 = __builtin_amdgcn_exp2f(EXACTQ ? (S[qt][8 * g + 2 * jj + 1] - sub) * c : S[qt][8 * g + 2 * jj + 1] - sub);
-                        const f32x2 pp = {p0, p1};
-                        const bf16x2 pb = __builtin_convertvector(pp, bf16x2);
-                        l += p0;
-                        l2 += p1;
-                        P[qt][g][2 * jj] = pb[0];
-                        P[qt][g][2 * jj + 1] = pb[1];
-                    }
-                return l + l2;
-            };
-            auto sm_fast = [&](int qt) {  // the common path: nothing to subtract
-                float l = 0.f, l2 = 0.f;
-#pragma unroll
-                for (int g = 0; g < 2; ++g)
-#pragma unroll
-                    for (int jj = 0; jj < 4; ++jj) {
-                        const float p0 = __builtin_amdgcn_exp2f(EXACTQ ? S[qt][8 * g + 2 * jj] * c : S[qt][8 * g + 2 * jj]);
-                        const float p1 = __builtin_amdgcn_exp2f(EXACTQ ? S[qt][8 * g + 2 * jj + 1] * c : S[qt][8 * g + 2 * jj + 1]);
-                        const f32x2 pp = {p0, p1};
-                        const bf16x2 pb = __builtin_convertvector(pp, bf16x2);
-                        l += p0;
-                        l2 += p1;
-                        P[qt][g][2 * jj] = pb[0];
-                        P[qt][g][2 * jj + 1] = pb[1];
-                    }
-                return l + l2;
-            };
-            // After SM(u): if some lane's sum reached the limit (or the unit is a block's first), take the unit's exact
-            // max, move the reference, rescale the block's accumulators and form P again.  S[qt] is still intact.
-            auto settle = [&](int qt, float l_unit, bool fresh) {
-                const bool bad = fresh || !(l_unit < kOptimisticLimit);
-                if (__builtin_amdgcn_ballot_w64(bad) != 0) {
-                    float a = S[qt][0];
-#pragma unroll
-                    for (int r = 1; r < 16; ++r) a = fmaxf(a, S[qt][r]);
-                    a = fmaxf(a, __shfl_xor(a, 32));          // relative to the current reference
-                    const float up = fresh ? a : fmaxf(a, 0.f);
-                    const float alpha = fresh ? 0.f : __builtin_amdgcn_exp2f(EXACTQ ? -up * c : -up);
-                    m_used[qt] = (fresh ? 0.f : m_used[qt]) + up;
-                    l_sum[qt] *= alpha;
-#pragma unroll
-                    for (int dt = 0; dt < 2; ++dt)
-#pragma unroll
-                        for (int r = 0; r < 16; ++r) o_acc[dt][qt][r] *= alpha;
-                    l_unit = sm_unit(qt, up);
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) minit[qt][r] = -m_used[qt];
-                }
-                l_sum[qt] += l_unit;
-            };
-            // PV of unit (kp, qp), then QK of unit (kq, qq): the order, the interleave ratio and wave priorities were
-            // swept on the chip; everything lies within 1 % (the loop is bound by vector issue, not by its schedule)
-            auto qk_pv = [&](int kq, int qq, int kp, int qp) {
-                pv(kp, qp);
-                qk(kq, qq);
-            };
-            // one MFMA : five or six vector instructions, eight times
-            auto interleave = [&]() {
-#pragma unroll
-                for (int i = 0; i < 8; ++i) {
-                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                    __builtin_amdgcn_sched_group_barrier(0x402, 6, 0);
-                }
-            };
-
-            read_k(t_begin, 0);
-            qk(0, 0);  // fill: QK of the first unit alone
-            for (int t = t_begin; t < t_pipe; ++t) {
-                const bool first = t == t_begin;
-                float lu;
-                // step (0,0): QK(0,1), PV(1,1) of the previous tile, SM(0,0)
-                __builtin_amdgcn_sched_barrier(0);
-                read_v(t, 0);
-                qk_pv(0, 1, 1, 1);
-                lu = sm_fast(0);
-                interleave();
-                __builtin_amdgcn_sched_barrier(0);
-                settle(0, lu, first);
-                bar(t);
-                // step (0,1): PV(0,0), QK(1,0), SM(0,1)
-                __builtin_amdgcn_sched_barrier(0);
-                read_k(t, 1);
-                qk_pv(1, 0, 0, 0);
-                lu = sm_fast(1);
-                interleave();
-                __builtin_amdgcn_sched_barrier(0);
-                settle(1, lu, first);
-                // step (1,0): QK(1,1), PV(0,1), SM(1,0)
-                __builtin_amdgcn_sched_barrier(0);
-                read_v(t, 1);
-                qk_pv(1, 1, 0, 1);
-                lu = sm_fast(0);
-                interleave();
-                __builtin_amdgcn_sched_barrier(0);
-                settle(0, lu, false);
-                // step (1,1): PV(1,0), QK(0,0) of the next tile (a discarded product after the last tile), SM(1,1)
-                __builtin_amdgcn_sched_barrier(0);
-                read_k(t + 1, 0);
-                qk_pv(0, 0, 1, 0);
-                lu = sm_fast(1);
-                interleave();
-                __builtin_amdgcn_sched_barrier(0);
-                settle(1, lu, false);
-            }
-            __builtin_amdgcn_sched_barrier(0);
-            pv(1, 1);  // drain: PV of the last unit
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        // tiles at the frame bounds (mask) and tiles only the later block sees: one tile at a time
-        auto run_rest = [&](int t_from, int t_to, auto qa_tag) {
-            constexpr int QA = decltype(qa_tag)::value;
-            for (int t = t_from; t < t_to; ++t) {
-                __builtin_amdgcn_sched_barrier(0);
-                bar(t);
-                if (QA == 0 || (wave_active && t * kBN < kmax_wave)) tile_body(t, (t - t_begin) & 3, qa_tag);
-            }
-        };
-        run_rest(t_pipe, t_mid, std::integral_constant<int, 0>{});
-        run_rest(t_mid, t_end, std::integral_constant<int, 1>{});
-        if (!wave_active) return;
-        if constexpr (EXACTQ)
-#pragma unroll
-            for (int qt = 0; qt < QT; ++qt) m_used[qt] *= c;
-        store_rows<QT>(p, wi, row, h, o_acc, l_sum, m_used);
-        return;
-    }
     // The tile loop runs twice in sequence for QT = 2: tiles in which both blocks of the wavefront have visible
     // keys, then the tiles only its later block still sees (two loops rather than a branch inside one: each keeps
     // its own, smaller, set of live registers).  Every wavefront passes the same number of barriers.

@@ -17,6 +17,7 @@
 
 #include "kernels_generic.hpp"
 #include "kernels_mfma.hpp"
+#include "kernels_mfma16.hpp"
 #include "kernels_mfma_bwd.hpp"
 
 struct nfd_attn {
@@ -325,11 +326,11 @@ static int fwd_impl(nfd_attn_t* h, const void* q, const void* k, const void* v, 
         else if (kv8)
             hipLaunchKernelGGL((nfd::mfma::attn_fwd_bf16_d64<1, true>), grid, block, 0, st, p);
         else if (lse && pl.block_m == nfd::mfma::kBM)  // training pair: scores from the queries as given
-            hipLaunchKernelGGL((nfd::mfma::attn_fwd_bf16_d64<2, false, true>), grid, block, 0, st, p);
+            hipLaunchKernelGGL((nfd::mfma::attn_fwd_bf16_d64_m16<true>), grid, block, 0, st, p);
         else if (lse)
             hipLaunchKernelGGL((nfd::mfma::attn_fwd_bf16_d64<1, false, true>), grid, block, 0, st, p);
         else if (pl.block_m == nfd::mfma::kBM)
-            hipLaunchKernelGGL((nfd::mfma::attn_fwd_bf16_d64<2, false>), grid, block, 0, st, p);
+            hipLaunchKernelGGL((nfd::mfma::attn_fwd_bf16_d64_m16<false>), grid, block, 0, st, p);
         else
             hipLaunchKernelGGL((nfd::mfma::attn_fwd_bf16_d64<1, false>), grid, block, 0, st, p);
         if (pl.n_splits > 1) {
