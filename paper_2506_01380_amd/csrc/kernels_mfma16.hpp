@@ -134,26 +134,21 @@ __device__ __forceinline__ void attn_fwd_item16(const FwdParams& p, const WorkIt
 #pragma unroll
         for (int r = 0; r < 16; ++r) o_acc[a][r] = 0.f;
     // Row sums.  MSUM (the plain forward): the second product also multiplies P^T by a block of ones, so the sum of a
-    // column of P - of the bf16 values the output is formed from - accumulates in the matrix pipe, in all four
-    // elements of l_acc[cq], and costs the vector unit nothing (the tile loop is bound by vector issue: 16 of its 48
-    // instructions per step were these adds).  The reference then sits kRefBias above the maximum seen, so that
+    // column of a unit's P - of the bf16 values the output is formed from - comes out of the matrix pipe (in all four
+    // elements of the result, in every lane group) and costs the vector unit one add per column instead of sixteen
+    // (the tile loop is bound by vector issue: 16 of its 48 instructions per step were these adds).  The result is
+    // added to l_sum at once rather than accumulated in place: four persistent registers per column do not fit.  The reference then sits kRefBias above the maximum seen, so that
     // "some P >= 2" (one bit of the packed values, OR-ed together) is a rare event that still leaves 2^119 of range.
     // EXACTQ (the training pair, whose log-sum-exp the backward normalises with) keeps fp32 sums of the unrounded
     // values on the vector unit and the test on them.
     constexpr bool MSUM = !EXACTQ;
     constexpr float kRefBias = MSUM ? 8.f : 0.f;
     float m_used[4], l_sum[4];  // [cq]; m_used in accumulator units (raw scores with EXACTQ)
-    f32x4 l_acc[4];
     bf16x8 ones;
 #pragma unroll
     for (int e = 0; e < 8; ++e) ones[e] = (__bf16)1.0f;
 #pragma unroll
-    for (int cq = 0; cq < 4; ++cq) {
-        m_used[cq] = kNegBig;
-        l_sum[cq] = 0.f;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) l_acc[cq][e] = 0.f;
-    }
+    for (int cq = 0; cq < 4; ++cq) { m_used[cq] = kNegBig; l_sum[cq] = 0.f; }
     // some value of the two packed operands is >= 2 (or not a number): bit 14 of a bf16 is the top exponent bit
     auto any_big = [](const bf16x8& a, const bf16x8& b) {
         const u32x4 x = __builtin_bit_cast(u32x4, a), y = __builtin_bit_cast(u32x4, b);
@@ -241,11 +236,11 @@ __device__ __forceinline__ void attn_fwd_item16(const FwdParams& p, const WorkIt
         return r;
     };
 
-    // ---- one whole tile at a time (tiles at the frame bounds, tiles only the later block sees) ---------------
-    // QA = first 32-row block of the wavefront that still has visible keys in this tile
-    auto tile_body = [&](int t, int slot, auto qa_tag) {
-        constexpr int QA = decltype(qa_tag)::value;
-        constexpr int C0 = 2 * QA;  // first query column block
+    // ---- one whole tile at a time (tiles at the frame bounds, tiles only the later block sees), one 32-row block
+    // of the wavefront per call: these tiles are few, and half the scores at a time keep the register peak of this
+    // path below that of the pipelined loop (a value that finds no register here is reloaded at every use, there too)
+    auto tile_body = [&](int t, int slot, auto qt_tag) {
+        constexpr int C0 = 2 * decltype(qt_tag)::value, C1 = C0 + 2;  // this block's query columns
         const int j0 = t * kBN;
         const __bf16* ks_ = sm.k[slot];
         const __bf16* vs_ = sm.v[slot];
@@ -260,7 +255,7 @@ __device__ __forceinline__ void attn_fwd_item16(const FwdParams& p, const WorkIt
 #pragma unroll
         for (int rb = 0; rb < 4; ++rb)
 #pragma unroll
-            for (int cq = C0; cq < 4; ++cq) {
+            for (int cq = C0; cq < C1; ++cq) {
 #pragma unroll
                 for (int e = 0; e < 4; ++e) s_acc[rb][cq][e] = 0.f;
 #pragma unroll
@@ -269,9 +264,9 @@ __device__ __forceinline__ void attn_fwd_item16(const FwdParams& p, const WorkIt
             }
         __builtin_amdgcn_sched_barrier(0);
         __builtin_amdgcn_s_setprio(0);
-        if (j0 + kBN > kmin_blk[QA]) {
+        if (j0 + kBN > kmin_blk[C0 / 2]) {
 #pragma unroll
-            for (int cq = C0; cq < 4; ++cq) {
+            for (int cq = C0; cq < C1; ++cq) {
                 const int left = kmax_lane_of(cq) - (j0 + 4 * sg(g));  // visible keys from this lane's first of the tile
 #pragma unroll
                 for (int rb = 0; rb < 4; ++rb)
@@ -284,7 +279,7 @@ __device__ __forceinline__ void attn_fwd_item16(const FwdParams& p, const WorkIt
         float l_tile[4];
         auto form_p = [&]() {
 #pragma unroll
-            for (int cq = C0; cq < 4; ++cq) {
+            for (int cq = C0; cq < C1; ++cq) {
                 const float mc = EXACTQ ? m_used[cq] * c : m_used[cq];
                 float l = 0.f, l2 = 0.f;
 #pragma unroll
@@ -308,10 +303,10 @@ __device__ __forceinline__ void attn_fwd_item16(const FwdParams& p, const WorkIt
 #pragma unroll
             for (int a = 0; a < 2; ++a)
 #pragma unroll
-                for (int b = C0; b < 4; ++b) asm volatile("" : "+v"(pf[a][b]));
+                for (int b = C0; b < C1; ++b) asm volatile("" : "+v"(pf[a][b]));
             bad = false;
 #pragma unroll
-            for (int cq = C0; cq < 4; ++cq) {
+            for (int cq = C0; cq < C1; ++cq) {
                 if constexpr (MSUM) bad |= any_big(pf[0][cq], pf[1][cq]);
                 else bad |= !(l_tile[cq] < kOptimisticLimit);
             }
@@ -323,7 +318,7 @@ __device__ __forceinline__ void attn_fwd_item16(const FwdParams& p, const WorkIt
             for (int fb = 0; fb < 4; ++fb) vf[kb][fb] = read_v_frag(vs_, kb, fb);
         if (__builtin_amdgcn_ballot_w64(bad) != 0) {
 #pragma unroll
-            for (int cq = C0; cq < 4; ++cq) {
+            for (int cq = C0; cq < C1; ++cq) {
                 float a = s_acc[0][cq][0];
 #pragma unroll
                 for (int rb = 0; rb < 4; ++rb)
@@ -335,7 +330,6 @@ __device__ __forceinline__ void attn_fwd_item16(const FwdParams& p, const WorkIt
                 const float alpha = __builtin_amdgcn_exp2f(EXACTQ ? (m_used[cq] - m_new) * c : m_used[cq] - m_new);
                 m_used[cq] = m_new;
                 l_sum[cq] *= alpha;
-                l_acc[cq] *= alpha;
 #pragma unroll
                 for (int r = 0; r < 16; ++r) o_acc[cq][r] *= alpha;
             }
@@ -343,18 +337,21 @@ __device__ __forceinline__ void attn_fwd_item16(const FwdParams& p, const WorkIt
         }
         if constexpr (!MSUM)
 #pragma unroll
-            for (int cq = C0; cq < 4; ++cq) l_sum[cq] += l_tile[cq];
+            for (int cq = C0; cq < C1; ++cq) l_sum[cq] += l_tile[cq];
         __builtin_amdgcn_sched_barrier(0);
         __builtin_amdgcn_s_setprio(PRIO);
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-            for (int cq = C0; cq < 4; ++cq) {
+            for (int cq = C0; cq < C1; ++cq) {
                 acc_mfma<0>(o_acc[cq], vf[kb][0], pf[kb][cq]);
                 acc_mfma<1>(o_acc[cq], vf[kb][1], pf[kb][cq]);
                 acc_mfma<2>(o_acc[cq], vf[kb][2], pf[kb][cq]);
                 acc_mfma<3>(o_acc[cq], vf[kb][3], pf[kb][cq]);
-                if constexpr (MSUM) l_acc[cq] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, pf[kb][cq], l_acc[cq], 0, 0, 0);
+                if constexpr (MSUM) {
+                    const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+                    l_sum[cq] += __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, pf[kb][cq], zero, 0, 0, 0)[0];
+                }
             }
         __builtin_amdgcn_sched_barrier(0);
     };
@@ -377,12 +374,12 @@ __device__ __forceinline__ void attn_fwd_item16(const FwdParams& p, const WorkIt
     const int t_mid = wave_active ? max(t_begin, min(t_end, (kmax_blk[0] + kBN - 1) / kBN)) : t_begin;
     int t_pipe = wave_active ? max(t_begin, min(t_mid, kmin_blk[0] / kBN)) : t_begin;
     if (t_pipe - t_begin < 2) t_pipe = t_begin;
-    auto bar = [&](int t) {
+    auto bar = [&](int t, auto load_slot) {  // load_slot: the ring slot of tile t + 3 (an int or a compile-time constant)
         if (t + 2 < t_end) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
         else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __builtin_amdgcn_s_barrier();
         __builtin_amdgcn_sched_barrier(0);
-        if (t + 3 < t_end) load_tile(t + 3, (t + 3 - t_begin) & 3);
+        if (t + 3 < t_end) load_tile(t + 3, (int)load_slot);
         // Key-split launches: the wave priority falls with the quarter of the chain the workgroup is in, so that of
         // two workgroups sharing a CU the one that lags is served first and both finish together (the arbiter
         // otherwise prefers the older one throughout: 52 against 70 us at four speculative frames).  Training
@@ -418,15 +415,15 @@ __device__ __forceinline__ void attn_fwd_item16(const FwdParams& p, const WorkIt
         for (int fb = 0; fb < 4; ++fb)
 #pragma unroll
             for (int e = 0; e < 8; ++e) vf[1][fb][e] = (__bf16)0.f;  // the first step's PV adds 0 . 0
-        auto read_k = [&](int t, int kb) {
-            const __bf16* ks_ = sm.k[(t - t_begin) & 3] + 32 * kb * kD;
+        auto read_k = [&](int slot, int kb) {
+            const __bf16* ks_ = sm.k[slot] + 32 * kb * kD;
 #pragma unroll
             for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
                 for (int ks = 0; ks < 2; ++ks) kf[kb][rb][ks] = lds_read_b128(ks_ + 16 * rb * kD + k_off[ks]);
         };
-        auto read_v = [&](int t, int kb) {
-            const __bf16* vs_ = sm.v[(t - t_begin) & 3];
+        auto read_v = [&](int slot, int kb) {
+            const __bf16* vs_ = sm.v[slot];
 #pragma unroll
             for (int fb = 0; fb < 4; ++fb) vf[kb][fb] = read_v_frag(vs_, kb, fb);
         };
@@ -443,13 +440,18 @@ __device__ __forceinline__ void attn_fwd_item16(const FwdParams& p, const WorkIt
                     S[qt][rb][cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[kb][rb][1], qf[2 * qt + cb][1], S[qt][rb][cb], 0, 0, 0);
         };
         auto pv = [&](int kb, int qt) {
+            if constexpr (MSUM) {  // the unit's column sums first: their adds then find room later in the same step
+                const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int cb = 0; cb < 2; ++cb)
+                    l_sum[2 * qt + cb] += __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, P[qt][cb], zero, 0, 0, 0)[0];
+            }
 #pragma unroll
             for (int cb = 0; cb < 2; ++cb) {
                 acc_mfma<0>(o_acc[2 * qt + cb], vf[kb][0], P[qt][cb]);
                 acc_mfma<1>(o_acc[2 * qt + cb], vf[kb][1], P[qt][cb]);
                 acc_mfma<2>(o_acc[2 * qt + cb], vf[kb][2], P[qt][cb]);
                 acc_mfma<3>(o_acc[2 * qt + cb], vf[kb][3], P[qt][cb]);
-                if constexpr (MSUM) l_acc[2 * qt + cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, P[qt][cb], l_acc[2 * qt + cb], 0, 0, 0);
             }
         };
         // softmax of one unit: P[qt][cb] from S[qt][.][cb] minus `sub[cb]` (accumulator units); lu: the lane's sums
@@ -492,13 +494,12 @@ __device__ __forceinline__ void attn_fwd_item16(const FwdParams& p, const WorkIt
                     a = fmaxf(a, __shfl_xor(a, 32));  // relative to the current reference
                     up[cb] = fresh ? a + kRefBias : fmaxf(a + kRefBias, 0.f);
                     const float alpha = fresh ? 0.f : __builtin_amdgcn_exp2f(EXACTQ ? -up[cb] * c : -up[cb]);
-                    m_used[cq] = (fresh ? 0.f : m_used[cq]) + up[cb];
+                    const float ref = (fresh ? 0.f : -minit[cq][0]) + up[cb];  // the reference lives in minit alone here
                     l_sum[cq] *= alpha;
-                    l_acc[cq] *= alpha;
-#pragma unroll
+    #pragma unroll
                     for (int r = 0; r < 16; ++r) o_acc[cq][r] *= alpha;
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) minit[cq][e] = -m_used[cq];
+                    for (int e = 0; e < 4; ++e) minit[cq][e] = -ref;
                 }
                 sm_unit(qt, up, lu, true);
             }
@@ -522,23 +523,24 @@ __device__ __forceinline__ void attn_fwd_item16(const FwdParams& p, const WorkIt
             }
         };
 
-        read_k(t_begin, 0);
-        qk(0, 0);  // fill: QK of the first unit alone
-        for (int t = t_begin; t < t_pipe; ++t) {
-            const bool first = t == t_begin;
+        // The four steps of one key tile in ring slot `slot`.  The main loop below runs four tiles per round with the
+        // slots as compile-time constants: every LDS address is then a per-lane offset fixed before the loop plus an
+        // immediate, and the round spends no vector instruction on addresses.  Up to three tiles remain for the
+        // second loop, which computes its slots.
+        auto tile_steps = [&](int t, auto slot, auto slot_next, auto slot_load, bool first) __attribute__((always_inline)) {
             float lu[2];
             // step (0,0): QK(0,1), PV(1,1) of the previous tile, SM(0,0)
             __builtin_amdgcn_sched_barrier(0);
-            read_v(t, 0);
             qk_pv(0, 1, 1, 1);
             sm_unit(0, no_sub, lu, false);
             interleave();
             __builtin_amdgcn_sched_barrier(0);
             settle(0, lu, first);
-            bar(t);
+            bar(t, slot_load);
             // step (0,1): PV(0,0), QK(1,0), SM(0,1)
             __builtin_amdgcn_sched_barrier(0);
-            read_k(t, 1);
+            read_k((int)slot, 1);
+            read_v((int)slot, 0);
             qk_pv(1, 0, 0, 0);
             sm_unit(1, no_sub, lu, false);
             interleave();
@@ -546,7 +548,6 @@ __device__ __forceinline__ void attn_fwd_item16(const FwdParams& p, const WorkIt
             settle(1, lu, first);
             // step (1,0): QK(1,1), PV(0,1), SM(1,0)
             __builtin_amdgcn_sched_barrier(0);
-            read_v(t, 1);
             qk_pv(1, 1, 0, 1);
             sm_unit(0, no_sub, lu, false);
             interleave();
@@ -554,24 +555,45 @@ __device__ __forceinline__ void attn_fwd_item16(const FwdParams& p, const WorkIt
             settle(0, lu, false);
             // step (1,1): PV(1,0), QK(0,0) of the next tile (a discarded product after the last tile), SM(1,1)
             __builtin_amdgcn_sched_barrier(0);
-            read_k(t + 1, 0);
+            read_k((int)slot_next, 0);
+            read_v((int)slot, 1);
             qk_pv(0, 0, 1, 0);
             sm_unit(1, no_sub, lu, false);
             interleave();
             __builtin_amdgcn_sched_barrier(0);
             settle(1, lu, false);
+        };
+        read_k(0, 0);
+        qk(0, 0);  // fill: QK of the first unit alone
+        typedef std::integral_constant<int, 0> I0;
+        typedef std::integral_constant<int, 1> I1;
+        typedef std::integral_constant<int, 2> I2;
+        typedef std::integral_constant<int, 3> I3;
+        int t = t_begin;
+        for (; t + 4 <= t_pipe; t += 4) {
+            tile_steps(t, I0{}, I1{}, I3{}, t == t_begin);
+            tile_steps(t + 1, I1{}, I2{}, I0{}, false);
+            tile_steps(t + 2, I2{}, I3{}, I1{}, false);
+            tile_steps(t + 3, I3{}, I0{}, I2{}, false);
+        }
+        for (; t < t_pipe; ++t) {
+            const int slot = (t - t_begin) & 3;
+            tile_steps(t, slot, (slot + 1) & 3, (slot + 3) & 3, t == t_begin);
         }
         __builtin_amdgcn_sched_barrier(0);
         pv(1, 1);  // drain: PV of the last unit
         __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int cq = 0; cq < 4; ++cq) m_used[cq] = -minit[cq][0];
     }
     // tiles at the frame bounds (mask) and tiles only the later block sees: one tile at a time
     auto run_rest = [&](int t_from, int t_to, auto qa_tag) {
         constexpr int QA = decltype(qa_tag)::value;
         for (int t = t_from; t < t_to; ++t) {
             __builtin_amdgcn_sched_barrier(0);
-            bar(t);
-            if (QA == 0 || (wave_active && t * kBN < kmax_wave)) tile_body(t, (t - t_begin) & 3, qa_tag);
+            bar(t, (t + 3 - t_begin) & 3);
+            if (QA == 0) tile_body(t, (t - t_begin) & 3, std::integral_constant<int, 0>{});
+            if (QA == 0 || (wave_active && t * kBN < kmax_wave)) tile_body(t, (t - t_begin) & 3, std::integral_constant<int, 1>{});
         }
     };
     run_rest(t_pipe, t_mid, std::integral_constant<int, 0>{});
@@ -583,7 +605,7 @@ __device__ __forceinline__ void attn_fwd_item16(const FwdParams& p, const WorkIt
     for (int cq = 0; cq < 4; ++cq) {
         float l_row;
         if constexpr (MSUM) {
-            l_row = l_acc[cq][0];
+            l_row = l_sum[cq];  // every lane group holds the whole column's sum
         } else {
             l_row = l_sum[cq] + __shfl_xor(l_sum[cq], 16);
             l_row += __shfl_xor(l_row, 32);
