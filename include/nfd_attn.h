@@ -141,7 +141,7 @@ int nfd_block_causal_attn_fwd_lse(nfd_attn_t* h, const void* q, const void* k, c
  * q, out, dout, dq : [B, H, q_frames*T, D]     k, v, dk, dv : [B, H, F*T, D]     lse : [B, H, q_frames*T]
  * out and lse are the results of nfd_block_causal_attn_fwd_lse on the same q, k, v, scale.  Of dk and
  * dv only the first kv_frames*T rows of every head are written.  No atomics: results are
- * bit-reproducible.  Uses the handle's workspace (4 bytes per query row).
+ * bit-reproducible.  Uses the handle's workspace (8 bytes per query row on the matrix-core path, 4 on the general one).
  * Supported: as the forward - bf16 with D = 64 on the matrix-core path (tensors 16-byte aligned there),
  * every other D <= 256 and all fp32 shapes on a general fp32-arithmetic path (one wavefront per row, not
  * tuned).

@@ -6,7 +6,8 @@
 //   ds_ij = p_ij (dp_ij - delta_i)    dq_i = scale sum_j ds_ij k_j    dk_j = scale sum_i ds_ij q_i
 // Two launches, no atomics, bit-reproducible:
 //   attn_bwd_dq_bf16_d64   query-major, same decomposition and tile ring as the forward kernel; it also forms
-//                          delta_i = <do_i, o_i> of its rows (dout is in its registers anyway) and stores it
+//                          delta_i = <do_i, o_i> of its rows (dout is in its registers anyway) and stores -delta_i
+//                          and lse_i log2(e), the two per-row values in the form the dk/dv kernel consumes them
 //   attn_bwd_dkdv_bf16_d64 key-major: a wavefront owns 32 (or 64) keys and walks over the query tiles that see them
 // Both matrix kernels recompute the weights from the stored log-sum-exp, so no online softmax is
 // needed, and both keep the operand whose rows they own in registers for the whole kernel.  Tiles
@@ -31,7 +32,8 @@ struct BwdParams {
     const void* dout;    // [BH, Sq, D]
     const void* out;     // [BH, Sq, D] the forward's result
     const float* lse;    // [BH, Sq] natural log of the softmax denominator (from the forward call)
-    float* delta;        // [BH, Sq] <dout_i, out_i> (workspace): written by the dq kernel, read by the dk/dv kernel
+    float* neg_delta;    // [BH, Sq] -<dout_i, out_i> (workspace): written by the dq kernel, read by the dk/dv kernel
+    float* lse2;         // [BH, Sq] lse * log2(e) (workspace): likewise
     void* dq;            // [BH, Sq, D]
     void* dk;            // [BH, Scap, D], rows < Sk written
     void* dv;            // [BH, Scap, D], rows < Sk written
@@ -165,7 +167,10 @@ attn_bwd_dq_bf16_d64(BwdParams p) {
             for (int e = 0; e < 8; ++e) part = __builtin_fmaf((float)gf[qt][ks][e], (float)of[e], part);
         }
         dl[qt] = part + __shfl_xor(part, 32);
-        if (h == 0 && row[qt] < p.Sq) p.delta[(int64_t)wi.bh * p.Sq + row[qt]] = dl[qt];  // for the dk/dv kernel
+        if (h == 0 && row[qt] < p.Sq) {  // for the dk/dv kernel
+            p.neg_delta[(int64_t)wi.bh * p.Sq + row[qt]] = -dl[qt];
+            p.lse2[(int64_t)wi.bh * p.Sq + row[qt]] = lse2[qt];
+        }
     }
     const int kmin_wave = kmax_of_row(min(rw0, p.Sq - 1), p.T, p.P);
     const int kmax_wave = kmax_of_row(min(rw0 + 63, p.Sq - 1), p.T, p.P);
@@ -278,24 +283,32 @@ attn_bwd_dq_bf16_d64(BwdParams p) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// dk, dv: a workgroup owns 4 x 32 KT keys (KT = 1: 128 keys, two wavefronts per SIMD; KT = 2: 256 keys,
-// one wavefront per SIMD), walks over the 64-row query tiles that can see them (all rows from the first frame that sees the block's first key).
+// dk, dv: a workgroup owns 128 keys (4 wavefronts x 32, two wavefronts per SIMD) and walks over the 64-row query
+// tiles that can see them (all rows from the first frame that sees the block's first key).
 //   S = Q.K^T, dP = dO.V^T (A = Q / dO rows from LDS, B = K^T / V^T in registers)
 //   dV^T += dO^T.P, dK^T += Q^T.dS (A by transposing reads of the dO / Q tile, B = P / dS accumulators)
 // In the accumulator layout a lane holds ONE key column and 16 of a block's 32 query rows, so the
-// per-row log-sum-exp and delta come from LDS (four 16-byte reads each per 32-row block).
+// per-row values come from LDS (four 16-byte reads each per 32-row block), in the form the dq kernel left them:
+// lse log2(e), subtracted inside the exponent's fma, and -delta, which is what the dP accumulators start from
+// (the matrix instruction adds the product to it), so dP - delta costs no instruction.
 // Key j is visible to row i iff i >= rmin(j) = (floor(j/T) - P) T: one bound per lane, no division
 // in the loop.
+//
+// A query tile is two units of 32 rows; unit u runs scores(u): 8 MFMA for S and dP; weights(u): 16 x (fma, exp2,
+// mul) + 16 packed conversions; grads(u): 8 MFMA for dV and dK.  (Measured and not kept: interleaving the matrix
+// instructions of one unit with the vector instructions of the other inside the wavefront, no gain - the second
+// wavefront of the SIMD already fills those slots; 64 keys per wavefront with one wavefront per SIMD, slower.)
+// ring depth: tiles t+1, t+2 in flight or landed while tile t is worked on, t+3 requested (three slots: 1 % slower;
+// three slots and three wavefronts per SIMD, which the registers allow with ten spills: 3 % slower)
+constexpr int kBwdKvSlots = 4;
 struct __attribute__((aligned(16))) SmemBwdKv {
-    __bf16 q[3][kTileElems];
-    __bf16 g[3][kTileElems];
-    float ld[3][4][64];  // per slot: [0] lse * log2e source values, [1] delta, [2], [3] padding loads
+    __bf16 q[kBwdKvSlots][kTileElems];
+    __bf16 g[kBwdKvSlots][kTileElems];
+    float ld[kBwdKvSlots][4][64];  // per slot: [0] lse * log2e, [1] -delta, [2], [3] the other two wavefronts' copies
 };
 
-template <int KT>
-__global__ void __launch_bounds__(256, KT == 1 ? 2 : 1)
+__global__ void __launch_bounds__(256, 2)
 attn_bwd_dkdv_bf16_d64(BwdParams p) {
-    constexpr int KW = 32 * KT;  // keys per wavefront
     __shared__ SmemBwdKv sm;
     const BwdItem wi = decode_bwd(p.BH, p.n_k_blocks);
     if (!wi.valid) return;
@@ -304,45 +317,39 @@ attn_bwd_dkdv_bf16_d64(BwdParams p) {
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n = lane & 31, h = lane >> 5;
-    const int k0 = k_block * (4 * KW);
-    const int kw0 = k0 + wave * KW;
+    const int k0 = k_block * 128;
+    const int kw0 = k0 + wave * 32;
 
     const __bf16* qg = (const __bf16*)p.q + (int64_t)wi.bh * p.Sq * kD;
     const __bf16* gg = (const __bf16*)p.dout + (int64_t)wi.bh * p.Sq * kD;
     const __bf16* kg = (const __bf16*)p.k + (int64_t)wi.bh * p.Scap * kD;
     const __bf16* vg = (const __bf16*)p.v + (int64_t)wi.bh * p.Scap * kD;
-    const float* lse_g = p.lse + (int64_t)wi.bh * p.Sq;
-    const float* dl_g = p.delta + (int64_t)wi.bh * p.Sq;
+    const float* lse_g = p.lse2 + (int64_t)wi.bh * p.Sq;
+    const float* dl_g = p.neg_delta + (int64_t)wi.bh * p.Sq;
 
     // ---- this wavefront's keys: B operands K^T, V^T and the visibility bound of the lane's key ----
-    int key[KT], rmin_lane[KT];
-    bf16x8 kf[KT][4], vf[KT][4];
+    const int key = kw0 + n;
+    const int kc = min(key, p.Sk - 1);           // ragged tail: a duplicate column, never stored
+    const int rmin_lane = (kc / p.T - p.P) * p.T;  // <= 0: visible to every row
+    bf16x8 kf[4], vf[4];
 #pragma unroll
-    for (int kt = 0; kt < KT; ++kt) {
-        key[kt] = kw0 + 32 * kt + n;
-        const int kc = min(key[kt], p.Sk - 1);  // ragged tail: a duplicate column, never stored
-        rmin_lane[kt] = (kc / p.T - p.P) * p.T;  // <= 0: visible to every row
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            kf[kt][ks] = *(const bf16x8*)(kg + (int64_t)kc * kD + 16 * ks + 8 * h);
-            vf[kt][ks] = *(const bf16x8*)(vg + (int64_t)kc * kD + 16 * ks + 8 * h);
-        }
+    for (int ks = 0; ks < 4; ++ks) {
+        kf[ks] = *(const bf16x8*)(kg + (int64_t)kc * kD + 16 * ks + 8 * h);
+        vf[ks] = *(const bf16x8*)(vg + (int64_t)kc * kD + 16 * ks + 8 * h);
     }
     const bool wave_active = kw0 < p.Sk;
-    const int kw_first = min(kw0, p.Sk - 1), kw_last = min(kw0 + KW - 1, p.Sk - 1);
+    const int kw_first = min(kw0, p.Sk - 1), kw_last = min(kw0 + 31, p.Sk - 1);
     const int rmin_wave = (kw_first / p.T - p.P) * p.T;  // tiles ending at or below it are skipped by this wavefront
     const int rmax_wave = (kw_last / p.T - p.P) * p.T;   // tiles starting at or above it need no mask
     const int rmin_wg = max(0, (k0 / p.T - p.P) * p.T);
     const int t_begin = rmin_wg / 64;
     const int t_end = (p.Sq + 63) / 64;
 
-    f32x16 dk_acc[2][KT], dv_acc[2][KT];  // [dt][kt]
+    f32x16 dk_acc[2], dv_acc[2];  // [dt]
 #pragma unroll
     for (int a = 0; a < 2; ++a)
 #pragma unroll
-        for (int b = 0; b < KT; ++b)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) { dk_acc[a][b][r] = 0.f; dv_acc[a][b][r] = 0.f; }
+        for (int r = 0; r < 16; ++r) { dk_acc[a][r] = 0.f; dv_acc[a][r] = 0.f; }
     const float c = p.scale_log2e;
 
     const int ld_row = 8 * wave + (lane >> 3);
@@ -350,7 +357,7 @@ attn_bwd_dkdv_bf16_d64(BwdParams p) {
     const unsigned lds_q0 = (unsigned)(size_t)(__attribute__((address_space(3))) char*)(&sm.q[0][0]) + wave * 1024;
     const unsigned lds_g0 = (unsigned)(size_t)(__attribute__((address_space(3))) char*)(&sm.g[0][0]) + wave * 1024;
     const unsigned lds_ld0 = (unsigned)(size_t)(__attribute__((address_space(3))) char*)(&sm.ld[0][0][0]) + wave * 256;
-    const float* row_vec = (wave & 1) ? dl_g : lse_g;  // wavefronts 0, 2 fetch the log-sum-exp, 1, 3 the delta
+    const float* row_vec = (wave & 1) ? dl_g : lse_g;  // wavefronts 0, 2 fetch lse log2(e), 1, 3 -delta
     auto load_tile = [&](int t, int slot) {  // five loads per wavefront and tile
         dma_tile_pair(qg, gg, t * 64, p.Sq, lds_q0 + slot * kTileElems * 2, lds_g0 + slot * kTileElems * 2, ld_row, ld_chunk);
         const int r = min(t * 64 + lane, p.Sq - 1);
@@ -358,28 +365,33 @@ attn_bwd_dkdv_bf16_d64(BwdParams p) {
     };
     const FragOffsets fo = frag_offsets(lane);
 
-    if (t_begin < t_end) load_tile(t_begin, 0);
-    if (t_begin + 1 < t_end) load_tile(t_begin + 1, 1);
+#pragma unroll
+    for (int i = 0; i < kBwdKvSlots - 1; ++i)
+        if (t_begin + i < t_end) load_tile(t_begin + i, i);
     wait_vmem_all();
 
-    int slot = 0;
+    int slot = 0, slot_load = kBwdKvSlots - 1;
     for (int t = t_begin; t < t_end; ++t) {
+        // tile t has landed for this wavefront once only the loads of later tiles (five each) are in flight; after the
+        // barrier it has landed for all, and every wavefront is done with tile t-1, whose slot tile t+3 takes
         __builtin_amdgcn_sched_barrier(0);
-        if (t + 1 < t_end) asm volatile("s_waitcnt vmcnt(5)" ::: "memory");
+        if (kBwdKvSlots > 3 && t + 2 < t_end) asm volatile("s_waitcnt vmcnt(10)" ::: "memory");
+        else if (t + 1 < t_end) asm volatile("s_waitcnt vmcnt(5)" ::: "memory");
         else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __builtin_amdgcn_s_barrier();
         __builtin_amdgcn_sched_barrier(0);
-        const int slot2 = slot == 0 ? 2 : slot - 1;
-        if (t + 2 < t_end) load_tile(t + 2, slot2);
+        if (t + kBwdKvSlots - 1 < t_end) load_tile(t + kBwdKvSlots - 1, slot_load);
         const int i0 = t * 64;
         if (wave_active && i0 + 64 > rmin_wave) {
             const __bf16* qs_ = sm.q[slot];
             const __bf16* gs_ = sm.g[slot];
             const bool need_mask = i0 < rmax_wave;
             const bool ragged = i0 + 64 > p.Sq;
-#pragma unroll
-            for (int qb = 0; qb < 2; ++qb) {  // 32 query rows at a time
-                f32x16 s_acc[KT], dp_acc[KT];   // [kt]
+            f32x16 s_acc[2], dp_acc[2];  // [qb]: the two 32-row units of the tile (one after the other)
+            f32x4 lse4[2][4];            // [qb][g4]
+            bf16x8 pk[2][2], dsk[2][2];  // [qb][g]: P and dS as operands of the second products
+            // rows of this lane in unit qb: i0 + 32 qb + 8 g4 + 4 h + e, g4 = 0..3, e = 0..3: accumulator element 4 g4 + e
+            auto scores = [&](int qb) {
                 bf16x8 qa[4], ga[4];
 #pragma unroll
                 for (int ks = 0; ks < 4; ++ks) {
@@ -387,80 +399,73 @@ attn_bwd_dkdv_bf16_d64(BwdParams p) {
                     ga[ks] = lds_read_b128(gs_ + 32 * qb * kD + fo.row_frag[ks]);
                 }
 #pragma unroll
-                for (int kt = 0; kt < KT; ++kt)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) { s_acc[kt][r] = 0.f; dp_acc[kt][r] = 0.f; }
-#pragma unroll
-                for (int ks = 0; ks < 4; ++ks)
-#pragma unroll
-                    for (int kt = 0; kt < KT; ++kt) {
-                        s_acc[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa[ks], kf[kt][ks], s_acc[kt], 0, 0, 0);
-                        dp_acc[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ga[ks], vf[kt][ks], dp_acc[kt], 0, 0, 0);
-                    }
-                // rows of this lane: i0 + 32 qb + 8 g4 + 4 h + e, g4 = 0..3, e = 0..3
-                f32x4 lse4[4], dl4[4];
-#pragma unroll
                 for (int g4 = 0; g4 < 4; ++g4) {
-                    lse4[g4] = *(const f32x4*)(&sm.ld[slot][0][32 * qb + 8 * g4 + 4 * h]) * kLog2e;
-                    dl4[g4] = *(const f32x4*)(&sm.ld[slot][1][32 * qb + 8 * g4 + 4 * h]);
+                    lse4[qb][g4] = *(const f32x4*)(&sm.ld[slot][0][32 * qb + 8 * g4 + 4 * h]);
+                    const f32x4 nd = *(const f32x4*)(&sm.ld[slot][1][32 * qb + 8 * g4 + 4 * h]);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) dp_acc[qb][4 * g4 + e] = nd[e];  // dP starts at -delta
                 }
+#pragma unroll
+                for (int r = 0; r < 16; ++r) s_acc[qb][r] = 0.f;
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks) {
+                    s_acc[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa[ks], kf[ks], s_acc[qb], 0, 0, 0);
+                    dp_acc[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ga[ks], vf[ks], dp_acc[qb], 0, 0, 0);
+                }
+            };
+            auto weights = [&](int qb) {
                 if (need_mask || ragged) {  // wave-uniform: rows the lane's key may not see, and the clamped
                                             // duplicate rows of a ragged last tile
 #pragma unroll
-                    for (int kt = 0; kt < KT; ++kt)
-#pragma unroll
-                        for (int r = 0; r < 16; ++r) {
-                            const int i = i0 + 32 * qb + 8 * (r >> 2) + 4 * h + (r & 3);
-                            if (i < rmin_lane[kt] || i >= p.Sq) s_acc[kt][r] = -INFINITY;
-                        }
+                    for (int r = 0; r < 16; ++r) {
+                        const int i = i0 + 32 * qb + 8 * (r >> 2) + 4 * h + (r & 3);
+                        if (i < rmin_lane || i >= p.Sq) s_acc[qb][r] = -INFINITY;
+                    }
                 }
 #pragma unroll
-                for (int kt = 0; kt < KT; ++kt)
+                for (int r = 0; r < 16; ++r) {
+                    const float pr = __builtin_amdgcn_exp2f(__builtin_fmaf(s_acc[qb][r], c, -lse4[qb][r >> 2][r & 3]));
+                    s_acc[qb][r] = pr;                   // P
+                    dp_acc[qb][r] = pr * dp_acc[qb][r];  // dS = P (dP - delta)
+                }
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const float pr = __builtin_amdgcn_exp2f(__builtin_fmaf(s_acc[kt][r], c, -lse4[r >> 2][r & 3]));
-                        s_acc[kt][r] = pr;                                                // P
-                        dp_acc[kt][r] = pr * (dp_acc[kt][r] - dl4[r >> 2][r & 3]);        // dS
-                    }
+                for (int g = 0; g < 2; ++g) { pk[qb][g] = pack8(s_acc[qb], g); dsk[qb][g] = pack8(dp_acc[qb], g); }
+            };
+            auto grads = [&](int qb) {
 #pragma unroll
-                for (int g = 0; g < 2; ++g) {
-                    bf16x8 pk[KT], dk_[KT];
-#pragma unroll
-                    for (int kt = 0; kt < KT; ++kt) { pk[kt] = pack8(s_acc[kt], g); dk_[kt] = pack8(dp_acc[kt], g); }
+                for (int g = 0; g < 2; ++g)
 #pragma unroll
                     for (int dt = 0; dt < 2; ++dt) {
                         const bf16x8 gt = read_tr_frag(gs_, fo, qb, g, dt);  // dO^T
                         const bf16x8 qt = read_tr_frag(qs_, fo, qb, g, dt);  // Q^T
-#pragma unroll
-                        for (int kt = 0; kt < KT; ++kt) {
-                            dv_acc[dt][kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gt, pk[kt], dv_acc[dt][kt], 0, 0, 0);
-                            dk_acc[dt][kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qt, dk_[kt], dk_acc[dt][kt], 0, 0, 0);
-                        }
+                        dv_acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gt, pk[qb][g], dv_acc[dt], 0, 0, 0);
+                        dk_acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qt, dsk[qb][g], dk_acc[dt], 0, 0, 0);
                     }
-                }
+            };
+#pragma unroll
+            for (int qb = 0; qb < 2; ++qb) {
+                scores(qb);
+                weights(qb);
+                grads(qb);
             }
         }
-        slot = slot == 2 ? 0 : slot + 1;
+        slot = slot == kBwdKvSlots - 1 ? 0 : slot + 1;
+        slot_load = slot_load == kBwdKvSlots - 1 ? 0 : slot_load + 1;
     }
 
-    if (!wave_active) return;
+    if (!wave_active || key >= p.Sk) return;
+    __bf16* dkg = (__bf16*)p.dk + ((int64_t)wi.bh * p.Scap + key) * kD;
+    __bf16* dvg = (__bf16*)p.dv + ((int64_t)wi.bh * p.Scap + key) * kD;
 #pragma unroll
-    for (int kt = 0; kt < KT; ++kt) {
-        if (key[kt] >= p.Sk) continue;
-        __bf16* dkg = (__bf16*)p.dk + ((int64_t)wi.bh * p.Scap + key[kt]) * kD;
-        __bf16* dvg = (__bf16*)p.dv + ((int64_t)wi.bh * p.Scap + key[kt]) * kD;
+    for (int dt = 0; dt < 2; ++dt)
 #pragma unroll
-        for (int dt = 0; dt < 2; ++dt)
-#pragma unroll
-            for (int rb = 0; rb < 4; ++rb) {
-                const f32x4 xk = {dk_acc[dt][kt][4 * rb] * p.scale, dk_acc[dt][kt][4 * rb + 1] * p.scale,
-                                  dk_acc[dt][kt][4 * rb + 2] * p.scale, dk_acc[dt][kt][4 * rb + 3] * p.scale};
-                const f32x4 xv = {dv_acc[dt][kt][4 * rb], dv_acc[dt][kt][4 * rb + 1], dv_acc[dt][kt][4 * rb + 2],
-                                  dv_acc[dt][kt][4 * rb + 3]};
-                *(bf16x4*)(dkg + 32 * dt + 8 * rb + 4 * h) = __builtin_convertvector(xk, bf16x4);
-                *(bf16x4*)(dvg + 32 * dt + 8 * rb + 4 * h) = __builtin_convertvector(xv, bf16x4);
-            }
-    }
+        for (int rb = 0; rb < 4; ++rb) {
+            const f32x4 xk = {dk_acc[dt][4 * rb] * p.scale, dk_acc[dt][4 * rb + 1] * p.scale,
+                              dk_acc[dt][4 * rb + 2] * p.scale, dk_acc[dt][4 * rb + 3] * p.scale};
+            const f32x4 xv = {dv_acc[dt][4 * rb], dv_acc[dt][4 * rb + 1], dv_acc[dt][4 * rb + 2], dv_acc[dt][4 * rb + 3]};
+            *(bf16x4*)(dkg + 32 * dt + 8 * rb + 4 * h) = __builtin_convertvector(xk, bf16x4);
+            *(bf16x4*)(dvg + 32 * dt + 8 * rb + 4 * h) = __builtin_convertvector(xv, bf16x4);
+        }
 }
 
 }  // namespace mfma

@@ -517,18 +517,18 @@ int nfd_block_causal_attn_bwd(nfd_attn_t* h, const void* q, const void* k, const
     if (((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)out | (uintptr_t)dout | (uintptr_t)dq | (uintptr_t)dk |
          (uintptr_t)dv) % 16 != 0 || (uintptr_t)lse % 4 != 0)
         return fail(h, NFD_ERR_UNSUPPORTED, "tensors must be 16-byte aligned (lse 4-byte)");
-    if ((size_t)(BH * Sq) * sizeof(float) > h->workspace_bytes)
+    if ((size_t)(BH * Sq) * 2 * sizeof(float) > h->workspace_bytes)
         return fail(h, NFD_ERR_ALLOC, "the per-row workspace of the backward exceeds the handle's workspace");
     if (!(scale > 0.f)) scale = 1.0f / std::sqrt((float)D);
 
     nfd::mfma::BwdParams p{};
     p.q = q; p.k = k; p.v = v; p.dout = dout; p.out = out; p.lse = lse;
-    p.delta = (float*)h->workspace;
+    p.neg_delta = (float*)h->workspace;
+    p.lse2 = p.neg_delta + BH * Sq;
     p.dq = dq; p.dk = dk; p.dv = dv;
     p.BH = (int)BH; p.Sq = (int)Sq; p.Sk = (int)Sk; p.Scap = F * T; p.T = T; p.P = kv_frames - q_frames;
     p.n_q_tiles = (int)((Sq + nfd::mfma::kBM - 1) / nfd::mfma::kBM);
-    constexpr int kKeysPerWave = 32;  // 32: two wavefronts per SIMD; 64: one
-    p.n_k_blocks = (int)((Sk + 4 * kKeysPerWave - 1) / (4 * kKeysPerWave));
+    p.n_k_blocks = (int)((Sk + 127) / 128);  // 4 wavefronts x 32 keys
     p.scale = scale;
     p.scale_log2e = scale * nfd::kLog2e;
     if (BH * p.n_q_tiles > (int64_t)0x7fffffff || BH * p.n_k_blocks > (int64_t)0x7fffffff)
@@ -536,9 +536,9 @@ int nfd_block_causal_attn_bwd(nfd_attn_t* h, const void* q, const void* k, const
     if (const int dc = check_device(h)) return dc;
     hipStream_t st = (hipStream_t)stream;
     const unsigned heads8 = (unsigned)BH;  // one workgroup per (head, item)
-    // the dq kernel first: it writes the per-row delta that the dk/dv kernel reads
+    // the dq kernel first: it writes the two per-row vectors that the dk/dv kernel reads
     hipLaunchKernelGGL(nfd::mfma::attn_bwd_dq_bf16_d64, dim3(heads8 * p.n_q_tiles), dim3(256), 0, st, p);
-    hipLaunchKernelGGL(nfd::mfma::attn_bwd_dkdv_bf16_d64<kKeysPerWave / 32>, dim3(heads8 * p.n_k_blocks), dim3(256), 0, st, p);
+    hipLaunchKernelGGL(nfd::mfma::attn_bwd_dkdv_bf16_d64, dim3(heads8 * p.n_k_blocks), dim3(256), 0, st, p);
     return check_hip(h, hipGetLastError(), "backward launch");
 }
 
