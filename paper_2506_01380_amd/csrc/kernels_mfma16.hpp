@@ -147,6 +147,7 @@ __device__ __forceinline__ void attn_fwd_item16(const FwdParams& p, const WorkIt
     bf16x8 ones;
 #pragma unroll
     for (int e = 0; e < 8; ++e) ones[e] = (__bf16)1.0f;
+    asm volatile("" : "+v"(ones));  // keep it in registers: rebuilt from constants it costs two moves per step
 #pragma unroll
     for (int cq = 0; cq < 4; ++cq) { m_used[cq] = kNegBig; l_sum[cq] = 0.f; }
     // some value of the two packed operands is >= 2 (or not a number): bit 14 of a bf16 is the top exponent bit
