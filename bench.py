@@ -349,7 +349,7 @@ def main():
     else:
         roof = {"bound": "hbm", "achieved": round(main_res["gbs"], 1), "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": round(hbm_frac, 4)}
     roof.update({"traffic": traffic, "traffic_source": "profiles/hbm_traffic.json (rocprofv3 --pmc runs; not measured in this run)",
-                 "kernel": "attn_fwd_bf16_d64_m16",
+                 "kernel": "attn_fwd_bf16_d64_m16" if main_res["plan"]["block_m"] == 256 else "attn_fwd_bf16_d64<1>",
                  # both roofs, always: the algorithmic FLOPs against the matrix-core peak, the minimum bytes against HBM
                  "mfma": {"achieved_tflops": round(main_res["tflops"], 2), "peak": PEAK_BF16_TFLOPS, "frac": round(frac, 4)},
                  "hbm": {"achieved_gbs": round(main_res["gbs"], 1), "peak": PEAK_HBM_GBS, "frac": round(hbm_frac, 4),
