@@ -127,6 +127,15 @@ __device__ __forceinline__ bf16x8 pack8(const f32x16& a, int g) {
 // dq: a workgroup owns 256 query rows (4 wavefronts x 64), walks over the visible key tiles.
 //   S^T = K.Q^T, dP^T = V.dO^T (A = K / V rows from LDS, B = Q^T / dO^T in registers)
 //   dS^T = P^T o (dP^T - delta),  dQ^T += K^T.dS^T (A = K^T by transposing read, B = dS^T accumulators)
+// 16x16x32 shape of the matrix instruction, in the register layout of the forward kernel (kernels_mfma16.hpp): lane =
+// (j, g), j = lane % 16, g = lane / 16; a wavefront's 64 rows are four column blocks cq of 16 queries, a lane owns
+// query 16 cq + j of each; 32 keys at a time as two 16-key blocks, operand row i of a block being tile row
+// 4 sg(i / 4) + i % 4, sg = (0, 2, 3, 1).  The accumulators of S^T and dP^T give lane (j, g) keys 4 sg(g) .. + 3 of both
+// blocks: the eight values of dS^T it needs as B operand of the third product, whose A operand K^T comes from the
+// transposing read in the same key order.  The per-row values are per-lane scalars here: lse log2(e) goes into the
+// exponent's fma, and dP^T starts from -delta (a four-register C operand per column block, kept for the whole kernel),
+// so dP - delta costs no instruction.  The four column blocks are worked one after the other on the same K, V and K^T
+// fragments: a quarter of the scores live at a time.
 __global__ void __launch_bounds__(256, 2)
 attn_bwd_dq_bf16_d64(BwdParams p) {
     __shared__ SmemRing sm;
@@ -136,7 +145,8 @@ attn_bwd_dq_bf16_d64(BwdParams p) {
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int n = lane & 31, h = lane >> 5;
+    const int j = lane & 15, g = lane >> 4;
+    auto sg = [](int x) { return (0x78 >> (2 * x)) & 3; };  // 0, 2, 3, 1
     const int r0 = q_tile * kBM;
     const int r_last = min(r0 + kBM, p.Sq) - 1;
     const int n_tiles = (kmax_of_row(r_last, p.T, p.P) + kBN - 1) / kBN;
@@ -148,41 +158,43 @@ attn_bwd_dq_bf16_d64(BwdParams p) {
     const __bf16* vg = (const __bf16*)p.v + (int64_t)wi.bh * p.Scap * kD;
 
     const int rw0 = r0 + wave * 64;
-    int row[2], kmax_lane[2];
-    float lse2[2], dl[2];
-    bf16x8 qf[2][4], gf[2][4];
+    float lse2[4];
+    f32x4 ndl[4];            // [cq] -delta of the lane's query in all four elements: the C operand dP^T starts from
+    bf16x8 qf[4][2], gf[4][2];  // [cq][ks]
 #pragma unroll
-    for (int qt = 0; qt < 2; ++qt) {
-        row[qt] = rw0 + 32 * qt + n;
-        const int rc = min(row[qt], p.Sq - 1);  // ragged tail: compute a duplicate, never store it
-        kmax_lane[qt] = kmax_of_row(rc, p.T, p.P);
-        lse2[qt] = p.lse[(int64_t)wi.bh * p.Sq + rc] * kLog2e;
-        float part = 0.f;  // this lane's half of <dout_i, out_i>: the features it holds of dout
+    for (int cq = 0; cq < 4; ++cq) {
+        const int row = rw0 + 16 * cq + j;
+        const int rc = min(row, p.Sq - 1);  // ragged tail: compute a duplicate, never store it
+        lse2[cq] = p.lse[(int64_t)wi.bh * p.Sq + rc] * kLog2e;
+        float part = 0.f;  // this lane's quarter of <dout_i, out_i>: the features it holds of dout
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            qf[qt][ks] = *(const bf16x8*)(qg + (int64_t)rc * kD + 16 * ks + 8 * h);
-            gf[qt][ks] = *(const bf16x8*)(gg + (int64_t)rc * kD + 16 * ks + 8 * h);
-            const bf16x8 of = *(const bf16x8*)(og_ + (int64_t)rc * kD + 16 * ks + 8 * h);
+        for (int ks = 0; ks < 2; ++ks) {
+            qf[cq][ks] = *(const bf16x8*)(qg + (int64_t)rc * kD + 32 * ks + 8 * g);
+            gf[cq][ks] = *(const bf16x8*)(gg + (int64_t)rc * kD + 32 * ks + 8 * g);
+            const bf16x8 of = *(const bf16x8*)(og_ + (int64_t)rc * kD + 32 * ks + 8 * g);
 #pragma unroll
-            for (int e = 0; e < 8; ++e) part = __builtin_fmaf((float)gf[qt][ks][e], (float)of[e], part);
+            for (int e = 0; e < 8; ++e) part = __builtin_fmaf((float)gf[cq][ks][e], (float)of[e], part);
         }
-        dl[qt] = part + __shfl_xor(part, 32);
-        if (h == 0 && row[qt] < p.Sq) {  // for the dk/dv kernel
-            p.neg_delta[(int64_t)wi.bh * p.Sq + row[qt]] = -dl[qt];
-            p.lse2[(int64_t)wi.bh * p.Sq + row[qt]] = lse2[qt];
+        part += __shfl_xor(part, 16);
+        const float dl = part + __shfl_xor(part, 32);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) ndl[cq][e] = -dl;
+        if (g == 0 && row < p.Sq) {  // for the dk/dv kernel
+            p.neg_delta[(int64_t)wi.bh * p.Sq + row] = -dl;
+            p.lse2[(int64_t)wi.bh * p.Sq + row] = lse2[cq];
         }
     }
     const int kmin_wave = kmax_of_row(min(rw0, p.Sq - 1), p.T, p.P);
     const int kmax_wave = kmax_of_row(min(rw0 + 63, p.Sq - 1), p.T, p.P);
     const bool wave_active = rw0 < p.Sq;
 
-    f32x16 dq_acc[2][2];  // [dt][qt]
+    f32x4 dq_acc[4][4];  // [cq][fb]: query 16 cq + j, features 16 fb + 4 g + e
 #pragma unroll
-    for (int a = 0; a < 2; ++a)
+    for (int a = 0; a < 4; ++a)
 #pragma unroll
-        for (int b = 0; b < 2; ++b)
+        for (int b = 0; b < 4; ++b)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) dq_acc[a][b][r] = 0.f;
+            for (int e = 0; e < 4; ++e) dq_acc[a][b][e] = 0.f;
     const float c = p.scale_log2e;
 
     const int ld_row = 8 * wave + (lane >> 3);
@@ -192,11 +204,22 @@ attn_bwd_dq_bf16_d64(BwdParams p) {
     auto load_tile = [&](int t, int slot) {
         dma_tile_pair(kg, vg, t * kBN, p.Sk, lds_k0 + slot * kTileElems * 2, lds_v0 + slot * kTileElems * 2, ld_row, ld_chunk);
     };
-    const FragOffsets fo = frag_offsets(lane);
+    // per-lane fragment offsets (elements) under the swizzle; blocks at + 16, + 32, + 48 rows have the same swizzle
+    const int a_row = 4 * sg(j >> 2) + (j & 3);
+    const int fa = chunk_swizzle(a_row);
+    int a_off[2];  // [ks]: rows of K / V as A operands
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) a_off[ks] = a_row * kD + 8 * ((4 * ks + g) ^ fa);
+    const int t_row = 4 * sg(g) + (j >> 2);
+    const int ft = chunk_swizzle(t_row);
+    int t_off[4];  // [fb]: transposed fragments of K
+#pragma unroll
+    for (int fb = 0; fb < 4; ++fb) t_off[fb] = t_row * kD + 8 * ((2 * fb + ((j & 3) >> 1)) ^ ft) + 4 * (j & 1);
+    const int key_lane = 4 * sg(g);  // first of the lane's four keys of a 16-key block
 
     if (0 < n_tiles) load_tile(0, 0);
     if (1 < n_tiles) load_tile(1, 1);
-    wait_vmem_all();  // q, dout, lse, delta fragments and the first tiles have landed (and the compiler knows it)
+    wait_vmem_all();  // q, dout, out, lse fragments and the first tiles have landed (and the compiler knows it)
 
     int slot = 0;
     for (int t = 0; t < n_tiles; ++t) {
@@ -215,51 +238,66 @@ attn_bwd_dq_bf16_d64(BwdParams p) {
             const __bf16* vs_ = sm.v[slot];
             const bool need_mask = j0 + kBN > kmin_wave;  // tile crosses some row's bound
 #pragma unroll
-            for (int kb = 0; kb < 2; ++kb) {  // 32 keys at a time: keeps the live accumulators at half
-                f32x16 s_acc[2], dp_acc[2];   // [qt]
-                bf16x8 kf[4], vf[4];
+            for (int kb = 0; kb < 2; ++kb) {  // 32 keys at a time
+                bf16x8 kf[2][2], vf[2][2];   // [key block][ks]
+                bf16x8 kt[4];                // [fb] K^T of the 32 keys
 #pragma unroll
-                for (int ks = 0; ks < 4; ++ks) {
-                    kf[ks] = lds_read_b128(ks_ + 32 * kb * kD + fo.row_frag[ks]);
-                    vf[ks] = lds_read_b128(vs_ + 32 * kb * kD + fo.row_frag[ks]);
+                for (int b2 = 0; b2 < 2; ++b2)
+#pragma unroll
+                    for (int ks = 0; ks < 2; ++ks) {
+                        kf[b2][ks] = lds_read_b128(ks_ + (32 * kb + 16 * b2) * kD + a_off[ks]);
+                        vf[b2][ks] = lds_read_b128(vs_ + (32 * kb + 16 * b2) * kD + a_off[ks]);
+                    }
+#pragma unroll
+                for (int fb = 0; fb < 4; ++fb) {
+                    const __bf16* tp = ks_ + 32 * kb * kD + t_off[fb];
+                    const s16x4 lo = lds_read_tr(tp);
+                    const s16x4 hi = lds_read_tr(tp + 16 * kD);
+                    typedef __attribute__((ext_vector_type(8))) short s16x8;
+                    kt[fb] = __builtin_bit_cast(bf16x8, (s16x8)__builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
                 }
 #pragma unroll
-                for (int qt = 0; qt < 2; ++qt)
+                for (int cq = 0; cq < 4; ++cq) {  // one column block of queries at a time: a quarter of the scores live
+                    f32x4 s_acc[2], dp_acc[2];    // [key block]
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) { s_acc[qt][r] = 0.f; dp_acc[qt][r] = 0.f; }
+                    for (int b2 = 0; b2 < 2; ++b2) {
 #pragma unroll
-                for (int ks = 0; ks < 4; ++ks)
-#pragma unroll
-                    for (int qt = 0; qt < 2; ++qt) {
-                        s_acc[qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], qf[qt][ks], s_acc[qt], 0, 0, 0);
-                        dp_acc[qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[ks], gf[qt][ks], dp_acc[qt], 0, 0, 0);
+                        for (int e = 0; e < 4; ++e) s_acc[b2][e] = 0.f;
+                        dp_acc[b2] = ndl[cq];
                     }
-                if (need_mask) {
 #pragma unroll
-                    for (int qt = 0; qt < 2; ++qt)
+                    for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
-                        for (int r = 0; r < 16; ++r) {
-                            const int key = j0 + 32 * kb + 8 * (r >> 2) + 4 * h + (r & 3);
-                            if (key >= kmax_lane[qt]) s_acc[qt][r] = -INFINITY;
+                        for (int b2 = 0; b2 < 2; ++b2) {
+                            s_acc[b2] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[b2][ks], qf[cq][ks], s_acc[b2], 0, 0, 0);
+                            dp_acc[b2] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[b2][ks], gf[cq][ks], dp_acc[b2], 0, 0, 0);
                         }
-                }
-                // dS^T = P^T o (dP^T - delta), written over the score accumulators
+                    if (need_mask) {
+                        const int left = kmax_of_row(min(rw0 + 16 * cq + j, p.Sq - 1), p.T, p.P) - (j0 + 32 * kb + key_lane);
 #pragma unroll
-                for (int qt = 0; qt < 2; ++qt)
+                        for (int b2 = 0; b2 < 2; ++b2)
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const float pr = __builtin_amdgcn_exp2f(__builtin_fmaf(s_acc[qt][r], c, -lse2[qt]));
-                        s_acc[qt][r] = pr * (dp_acc[qt][r] - dl[qt]);
+                            for (int e = 0; e < 4; ++e)
+                                if (16 * b2 + e >= left) s_acc[b2][e] = -INFINITY;
+                    }
+                    // dS^T = P^T o (dP^T - delta), written over the dP accumulators
+#pragma unroll
+                    for (int b2 = 0; b2 < 2; ++b2)
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const float pr = __builtin_amdgcn_exp2f(__builtin_fmaf(s_acc[b2][e], c, -lse2[cq]));
+                            dp_acc[b2][e] = pr * dp_acc[b2][e];
+                        }
+                    bf16x8 ds;  // positions 0..3 from the first key block, 4..7 from the second
+#pragma unroll
+                    for (int e = 0; e < 4; e += 2) {
+                        const f32x2 x = {dp_acc[0][e], dp_acc[0][e + 1]}, y = {dp_acc[1][e], dp_acc[1][e + 1]};
+                        const bf16x2 xb = __builtin_convertvector(x, bf16x2), yb = __builtin_convertvector(y, bf16x2);
+                        ds[e] = xb[0]; ds[e + 1] = xb[1]; ds[4 + e] = yb[0]; ds[5 + e] = yb[1];
                     }
 #pragma unroll
-                for (int g = 0; g < 2; ++g) {
-                    const bf16x8 ds0 = pack8(s_acc[0], g), ds1 = pack8(s_acc[1], g);
-#pragma unroll
-                    for (int dt = 0; dt < 2; ++dt) {
-                        const bf16x8 kt = read_tr_frag(ks_, fo, kb, g, dt);
-                        dq_acc[dt][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kt, ds0, dq_acc[dt][0], 0, 0, 0);
-                        dq_acc[dt][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kt, ds1, dq_acc[dt][1], 0, 0, 0);
-                    }
+                    for (int fb = 0; fb < 4; ++fb)
+                        dq_acc[cq][fb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kt[fb], ds, dq_acc[cq][fb], 0, 0, 0);
                 }
             }
         }
@@ -268,17 +306,15 @@ attn_bwd_dq_bf16_d64(BwdParams p) {
 
     if (!wave_active) return;
 #pragma unroll
-    for (int qt = 0; qt < 2; ++qt) {
-        if (row[qt] >= p.Sq) continue;
-        __bf16* og = (__bf16*)p.dq + ((int64_t)wi.bh * p.Sq + row[qt]) * kD;
+    for (int cq = 0; cq < 4; ++cq) {
+        const int row = rw0 + 16 * cq + j;
+        if (row >= p.Sq) continue;
+        __bf16* og = (__bf16*)p.dq + ((int64_t)wi.bh * p.Sq + row) * kD;
 #pragma unroll
-        for (int dt = 0; dt < 2; ++dt)
-#pragma unroll
-            for (int rb = 0; rb < 4; ++rb) {
-                const f32x4 x = {dq_acc[dt][qt][4 * rb] * p.scale, dq_acc[dt][qt][4 * rb + 1] * p.scale,
-                                 dq_acc[dt][qt][4 * rb + 2] * p.scale, dq_acc[dt][qt][4 * rb + 3] * p.scale};
-                *(bf16x4*)(og + 32 * dt + 8 * rb + 4 * h) = __builtin_convertvector(x, bf16x4);
-            }
+        for (int fb = 0; fb < 4; ++fb) {
+            const f32x4 x = dq_acc[cq][fb] * p.scale;
+            *(bf16x4*)(og + 16 * fb + 4 * g) = __builtin_convertvector(x, bf16x4);
+        }
     }
 }
 
@@ -287,17 +323,29 @@ attn_bwd_dq_bf16_d64(BwdParams p) {
 // tiles that can see them (all rows from the first frame that sees the block's first key).
 //   S = Q.K^T, dP = dO.V^T (A = Q / dO rows from LDS, B = K^T / V^T in registers)
 //   dV^T += dO^T.P, dK^T += Q^T.dS (A by transposing reads of the dO / Q tile, B = P / dS accumulators)
-// In the accumulator layout a lane holds ONE key column and 16 of a block's 32 query rows, so the
-// per-row values come from LDS (four 16-byte reads each per 32-row block), in the form the dq kernel left them:
+// In the accumulator layout a lane holds ONE key column per column block and four of a block's sixteen query rows, so
+// the per-row values come from LDS (one 16-byte read each per row block), in the form the dq kernel left them:
 // lse log2(e), subtracted inside the exponent's fma, and -delta, which is what the dP accumulators start from
 // (the matrix instruction adds the product to it), so dP - delta costs no instruction.
-// Key j is visible to row i iff i >= rmin(j) = (floor(j/T) - P) T: one bound per lane, no division
+// Key j is visible to row i iff i >= rmin(j) = (floor(j/T) - P) T: one bound per lane and column block, no division
 // in the loop.
 //
-// A query tile is two units of 32 rows; unit u runs scores(u): 8 MFMA for S and dP; weights(u): 16 x (fma, exp2,
-// mul) + 16 packed conversions; grads(u): 8 MFMA for dV and dK.  (Measured and not kept: interleaving the matrix
-// instructions of one unit with the vector instructions of the other inside the wavefront, no gain - the second
-// wavefront of the SIMD already fills those slots; 64 keys per wavefront with one wavefront per SIMD, slower.)
+// The 16x16x32 shape of the matrix instruction, in the register layout of the forward kernel (kernels_mfma16.hpp).
+// Lane = (j, g), j = lane % 16, g = lane / 16.  A wavefront's 32 keys are two column blocks ck of 16; a 32-row unit of a
+// query tile is two row blocks rb of 16.  Operand row i of a row block is tile row 4 sg(i / 4) + i % 4, sg = (0, 2, 3, 1)
+// (the order that keeps both kinds of fragment reads free of bank conflicts under the tile swizzle), so
+//   S[rb][ck], dP[rb][ck]   A = Q / dO rows (16-byte LDS reads), B = K^T / V^T (registers)
+//                           D: key 16 ck + j, rows 4 sg(g) + e of the block, e = 0..3
+//   dV^T[fb][ck], dK^T[fb][ck]  A = dO^T / Q^T (transposing reads: features 16 fb + j, rows at positions (g, 0..7) =
+//                           rows 4 sg(g) .. + 3 of the unit's first block, then of its second), B = P / dS: exactly the
+//                           eight values lane (j, g) holds of the unit's two blocks, packed
+//                           D: key 16 ck + j, features 16 fb + 4 g + e
+// A query tile is two units of 32 rows; per unit 16 MFMA for S and dP, 16 x (fma, exp2, mul) + 16 packed conversions,
+// 16 MFMA for dV and dK, 20 KB of LDS fragment reads.  (The same kernel on the 32x32x16 instruction - 16 of a block's
+// 32 rows per lane, 24 KB of reads per unit - measured 0.835 against 0.804 ms for the whole backward at 16 frames of
+// 336 tokens.  Also measured there and not kept: interleaving the matrix instructions of one unit with the vector
+// instructions of the other inside the wavefront, no gain - the second wavefront of the SIMD already fills those
+// slots; 64 keys per wavefront with one wavefront per SIMD, slower.)
 // ring depth: tiles t+1, t+2 in flight or landed while tile t is worked on, t+3 requested (three slots: 1 % slower;
 // three slots and three wavefronts per SIMD, which the registers allow with ten spills: 3 % slower)
 constexpr int kBwdKvSlots = 4;
@@ -316,7 +364,8 @@ attn_bwd_dkdv_bf16_d64(BwdParams p) {
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int n = lane & 31, h = lane >> 5;
+    const int j = lane & 15, g = lane >> 4;
+    auto sg = [](int x) { return (0x78 >> (2 * x)) & 3; };  // 0, 2, 3, 1
     const int k0 = k_block * 128;
     const int kw0 = k0 + wave * 32;
 
@@ -327,15 +376,19 @@ attn_bwd_dkdv_bf16_d64(BwdParams p) {
     const float* lse_g = p.lse2 + (int64_t)wi.bh * p.Sq;
     const float* dl_g = p.neg_delta + (int64_t)wi.bh * p.Sq;
 
-    // ---- this wavefront's keys: B operands K^T, V^T and the visibility bound of the lane's key ----
-    const int key = kw0 + n;
-    const int kc = min(key, p.Sk - 1);           // ragged tail: a duplicate column, never stored
-    const int rmin_lane = (kc / p.T - p.P) * p.T;  // <= 0: visible to every row
-    bf16x8 kf[4], vf[4];
+    // ---- this wavefront's keys: B operands K^T, V^T and the visibility bound of the lane's two keys ----
+    int key[2], rmin_lane[2];
+    bf16x8 kf[2][2], vf[2][2];  // [ck][ks]
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-        kf[ks] = *(const bf16x8*)(kg + (int64_t)kc * kD + 16 * ks + 8 * h);
-        vf[ks] = *(const bf16x8*)(vg + (int64_t)kc * kD + 16 * ks + 8 * h);
+    for (int ck = 0; ck < 2; ++ck) {
+        key[ck] = kw0 + 16 * ck + j;
+        const int kc = min(key[ck], p.Sk - 1);  // ragged tail: a duplicate column, never stored
+        rmin_lane[ck] = (kc / p.T - p.P) * p.T;  // <= 0: visible to every row
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            kf[ck][ks] = *(const bf16x8*)(kg + (int64_t)kc * kD + 32 * ks + 8 * g);
+            vf[ck][ks] = *(const bf16x8*)(vg + (int64_t)kc * kD + 32 * ks + 8 * g);
+        }
     }
     const bool wave_active = kw0 < p.Sk;
     const int kw_first = min(kw0, p.Sk - 1), kw_last = min(kw0 + 31, p.Sk - 1);
@@ -345,11 +398,13 @@ attn_bwd_dkdv_bf16_d64(BwdParams p) {
     const int t_begin = rmin_wg / 64;
     const int t_end = (p.Sq + 63) / 64;
 
-    f32x16 dk_acc[2], dv_acc[2];  // [dt]
+    f32x4 dk_acc[4][2], dv_acc[4][2];  // [fb][ck]
 #pragma unroll
-    for (int a = 0; a < 2; ++a)
+    for (int a = 0; a < 4; ++a)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) { dk_acc[a][r] = 0.f; dv_acc[a][r] = 0.f; }
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) { dk_acc[a][b][e] = 0.f; dv_acc[a][b][e] = 0.f; }
     const float c = p.scale_log2e;
 
     const int ld_row = 8 * wave + (lane >> 3);
@@ -363,7 +418,35 @@ attn_bwd_dkdv_bf16_d64(BwdParams p) {
         const int r = min(t * 64 + lane, p.Sq - 1);
         asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dword %0, off" ::"v"(row_vec + r), "s"(lds_ld0 + slot * 1024) : "memory", "m0");
     };
-    const FragOffsets fo = frag_offsets(lane);
+    // per-lane fragment offsets (elements) under the swizzle; blocks at + 16, + 32, + 48 rows have the same swizzle
+    const int a_row = 4 * sg(j >> 2) + (j & 3);
+    const int fa = chunk_swizzle(a_row);
+    int a_off[2];  // [ks]: rows of Q / dO as A operands
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) a_off[ks] = a_row * kD + 8 * ((4 * ks + g) ^ fa);
+    const int t_row = 4 * sg(g) + (j >> 2);
+    const int ft = chunk_swizzle(t_row);
+    int t_off[4];  // [fb]: transposed fragments of Q / dO
+#pragma unroll
+    for (int fb = 0; fb < 4; ++fb) t_off[fb] = t_row * kD + 8 * ((2 * fb + ((j & 3) >> 1)) ^ ft) + 4 * (j & 1);
+    const int vec_row = 4 * sg(g);  // first of the lane's four rows of a 16-row block
+    auto read_t = [&](const __bf16* tile, int qb, int fb) {
+        const __bf16* tp = tile + 32 * qb * kD + t_off[fb];
+        const s16x4 lo = lds_read_tr(tp);
+        const s16x4 hi = lds_read_tr(tp + 16 * kD);
+        typedef __attribute__((ext_vector_type(8))) short s16x8;
+        return __builtin_bit_cast(bf16x8, (s16x8)__builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+    };
+    auto pack2 = [&](const f32x4& a, const f32x4& b) {  // positions 0..3 from the first row block, 4..7 from the second
+        bf16x8 r;
+#pragma unroll
+        for (int e = 0; e < 4; e += 2) {
+            const f32x2 x = {a[e], a[e + 1]}, y = {b[e], b[e + 1]};
+            const bf16x2 xb = __builtin_convertvector(x, bf16x2), yb = __builtin_convertvector(y, bf16x2);
+            r[e] = xb[0]; r[e + 1] = xb[1]; r[4 + e] = yb[0]; r[5 + e] = yb[1];
+        }
+        return r;
+    };
 
 #pragma unroll
     for (int i = 0; i < kBwdKvSlots - 1; ++i)
@@ -372,8 +455,6 @@ attn_bwd_dkdv_bf16_d64(BwdParams p) {
 
     int slot = 0, slot_load = kBwdKvSlots - 1;
     for (int t = t_begin; t < t_end; ++t) {
-        // tile t has landed for this wavefront once only the loads of later tiles (five each) are in flight; after the
-        // barrier it has landed for all, and every wavefront is done with tile t-1, whose slot tile t+3 takes
         __builtin_amdgcn_sched_barrier(0);
         if (kBwdKvSlots > 3 && t + 2 < t_end) asm volatile("s_waitcnt vmcnt(10)" ::: "memory");
         else if (t + 1 < t_end) asm volatile("s_waitcnt vmcnt(5)" ::: "memory");
@@ -387,85 +468,93 @@ attn_bwd_dkdv_bf16_d64(BwdParams p) {
             const __bf16* gs_ = sm.g[slot];
             const bool need_mask = i0 < rmax_wave;
             const bool ragged = i0 + 64 > p.Sq;
-            f32x16 s_acc[2], dp_acc[2];  // [qb]: the two 32-row units of the tile (one after the other)
-            f32x4 lse4[2][4];            // [qb][g4]
-            bf16x8 pk[2][2], dsk[2][2];  // [qb][g]: P and dS as operands of the second products
-            // rows of this lane in unit qb: i0 + 32 qb + 8 g4 + 4 h + e, g4 = 0..3, e = 0..3: accumulator element 4 g4 + e
-            auto scores = [&](int qb) {
-                bf16x8 qa[4], ga[4];
-#pragma unroll
-                for (int ks = 0; ks < 4; ++ks) {
-                    qa[ks] = lds_read_b128(qs_ + 32 * qb * kD + fo.row_frag[ks]);
-                    ga[ks] = lds_read_b128(gs_ + 32 * qb * kD + fo.row_frag[ks]);
-                }
-#pragma unroll
-                for (int g4 = 0; g4 < 4; ++g4) {
-                    lse4[qb][g4] = *(const f32x4*)(&sm.ld[slot][0][32 * qb + 8 * g4 + 4 * h]);
-                    const f32x4 nd = *(const f32x4*)(&sm.ld[slot][1][32 * qb + 8 * g4 + 4 * h]);
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) dp_acc[qb][4 * g4 + e] = nd[e];  // dP starts at -delta
-                }
-#pragma unroll
-                for (int r = 0; r < 16; ++r) s_acc[qb][r] = 0.f;
-#pragma unroll
-                for (int ks = 0; ks < 4; ++ks) {
-                    s_acc[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa[ks], kf[ks], s_acc[qb], 0, 0, 0);
-                    dp_acc[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ga[ks], vf[ks], dp_acc[qb], 0, 0, 0);
-                }
-            };
-            auto weights = [&](int qb) {
-                if (need_mask || ragged) {  // wave-uniform: rows the lane's key may not see, and the clamped
-                                            // duplicate rows of a ragged last tile
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const int i = i0 + 32 * qb + 8 * (r >> 2) + 4 * h + (r & 3);
-                        if (i < rmin_lane || i >= p.Sq) s_acc[qb][r] = -INFINITY;
-                    }
-                }
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const float pr = __builtin_amdgcn_exp2f(__builtin_fmaf(s_acc[qb][r], c, -lse4[qb][r >> 2][r & 3]));
-                    s_acc[qb][r] = pr;                   // P
-                    dp_acc[qb][r] = pr * dp_acc[qb][r];  // dS = P (dP - delta)
-                }
-#pragma unroll
-                for (int g = 0; g < 2; ++g) { pk[qb][g] = pack8(s_acc[qb], g); dsk[qb][g] = pack8(dp_acc[qb], g); }
-            };
-            auto grads = [&](int qb) {
-#pragma unroll
-                for (int g = 0; g < 2; ++g)
-#pragma unroll
-                    for (int dt = 0; dt < 2; ++dt) {
-                        const bf16x8 gt = read_tr_frag(gs_, fo, qb, g, dt);  // dO^T
-                        const bf16x8 qt = read_tr_frag(qs_, fo, qb, g, dt);  // Q^T
-                        dv_acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gt, pk[qb][g], dv_acc[dt], 0, 0, 0);
-                        dk_acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qt, dsk[qb][g], dk_acc[dt], 0, 0, 0);
-                    }
-            };
 #pragma unroll
             for (int qb = 0; qb < 2; ++qb) {
-                scores(qb);
-                weights(qb);
-                grads(qb);
+                f32x4 s_acc[2][2], dp_acc[2][2];  // [rb][ck]
+                f32x4 lse4[2];                    // [rb]
+                bf16x8 qa[2][2], ga[2][2];        // [rb][ks]
+#pragma unroll
+                for (int rb = 0; rb < 2; ++rb) {
+#pragma unroll
+                    for (int ks = 0; ks < 2; ++ks) {
+                        qa[rb][ks] = lds_read_b128(qs_ + (32 * qb + 16 * rb) * kD + a_off[ks]);
+                        ga[rb][ks] = lds_read_b128(gs_ + (32 * qb + 16 * rb) * kD + a_off[ks]);
+                    }
+                    lse4[rb] = *(const f32x4*)(&sm.ld[slot][0][32 * qb + 16 * rb + vec_row]);
+                    const f32x4 nd = *(const f32x4*)(&sm.ld[slot][1][32 * qb + 16 * rb + vec_row]);
+#pragma unroll
+                    for (int ck = 0; ck < 2; ++ck) {
+                        dp_acc[rb][ck] = nd;  // dP starts at -delta
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) s_acc[rb][ck][e] = 0.f;
+                    }
+                }
+#pragma unroll
+                for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+                    for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+                        for (int ck = 0; ck < 2; ++ck) {
+                            s_acc[rb][ck] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qa[rb][ks], kf[ck][ks], s_acc[rb][ck], 0, 0, 0);
+                            dp_acc[rb][ck] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ga[rb][ks], vf[ck][ks], dp_acc[rb][ck], 0, 0, 0);
+                        }
+                if (need_mask || ragged) {  // wave-uniform: rows a lane's key may not see, and the clamped duplicate
+                                            // rows of a ragged last tile
+#pragma unroll
+                    for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const int i = i0 + 32 * qb + 16 * rb + vec_row + e;
+#pragma unroll
+                            for (int ck = 0; ck < 2; ++ck)
+                                if (i < rmin_lane[ck] || i >= p.Sq) s_acc[rb][ck][e] = -INFINITY;
+                        }
+                }
+#pragma unroll
+                for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+                    for (int ck = 0; ck < 2; ++ck)
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const float pr = __builtin_amdgcn_exp2f(__builtin_fmaf(s_acc[rb][ck][e], c, -lse4[rb][e]));
+                            s_acc[rb][ck][e] = pr;                         // P
+                            dp_acc[rb][ck][e] = pr * dp_acc[rb][ck][e];    // dS = P (dP - delta)
+                        }
+                bf16x8 pk[2], dsk[2];  // [ck]
+#pragma unroll
+                for (int ck = 0; ck < 2; ++ck) {
+                    pk[ck] = pack2(s_acc[0][ck], s_acc[1][ck]);
+                    dsk[ck] = pack2(dp_acc[0][ck], dp_acc[1][ck]);
+                }
+#pragma unroll
+                for (int fb = 0; fb < 4; ++fb) {
+                    const bf16x8 gt = read_t(gs_, qb, fb);  // dO^T
+                    const bf16x8 qt = read_t(qs_, qb, fb);  // Q^T
+#pragma unroll
+                    for (int ck = 0; ck < 2; ++ck) {
+                        dv_acc[fb][ck] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(gt, pk[ck], dv_acc[fb][ck], 0, 0, 0);
+                        dk_acc[fb][ck] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qt, dsk[ck], dk_acc[fb][ck], 0, 0, 0);
+                    }
+                }
             }
         }
         slot = slot == kBwdKvSlots - 1 ? 0 : slot + 1;
         slot_load = slot_load == kBwdKvSlots - 1 ? 0 : slot_load + 1;
     }
 
-    if (!wave_active || key >= p.Sk) return;
-    __bf16* dkg = (__bf16*)p.dk + ((int64_t)wi.bh * p.Scap + key) * kD;
-    __bf16* dvg = (__bf16*)p.dv + ((int64_t)wi.bh * p.Scap + key) * kD;
+    if (!wave_active) return;
 #pragma unroll
-    for (int dt = 0; dt < 2; ++dt)
+    for (int ck = 0; ck < 2; ++ck) {
+        if (key[ck] >= p.Sk) continue;
+        __bf16* dkg = (__bf16*)p.dk + ((int64_t)wi.bh * p.Scap + key[ck]) * kD;
+        __bf16* dvg = (__bf16*)p.dv + ((int64_t)wi.bh * p.Scap + key[ck]) * kD;
 #pragma unroll
-        for (int rb = 0; rb < 4; ++rb) {
-            const f32x4 xk = {dk_acc[dt][4 * rb] * p.scale, dk_acc[dt][4 * rb + 1] * p.scale,
-                              dk_acc[dt][4 * rb + 2] * p.scale, dk_acc[dt][4 * rb + 3] * p.scale};
-            const f32x4 xv = {dv_acc[dt][4 * rb], dv_acc[dt][4 * rb + 1], dv_acc[dt][4 * rb + 2], dv_acc[dt][4 * rb + 3]};
-            *(bf16x4*)(dkg + 32 * dt + 8 * rb + 4 * h) = __builtin_convertvector(xk, bf16x4);
-            *(bf16x4*)(dvg + 32 * dt + 8 * rb + 4 * h) = __builtin_convertvector(xv, bf16x4);
+        for (int fb = 0; fb < 4; ++fb) {
+            const f32x4 xk = dk_acc[fb][ck] * p.scale;
+            *(bf16x4*)(dkg + 16 * fb + 4 * g) = __builtin_convertvector(xk, bf16x4);
+            *(bf16x4*)(dvg + 16 * fb + 4 * g) = __builtin_convertvector(dv_acc[fb][ck], bf16x4);
         }
+    }
 }
 
 }  // namespace mfma
