@@ -8,7 +8,7 @@
 //   attn_bwd_dq_bf16_d64   query-major, same decomposition and tile ring as the forward kernel; it also forms
 //                          delta_i = <do_i, o_i> of its rows (dout is in its registers anyway) and stores -delta_i
 //                          and lse_i log2(e), the two per-row values in the form the dk/dv kernel consumes them
-//   attn_bwd_dkdv_bf16_d64 key-major: a wavefront owns 32 (or 64) keys and walks over the query tiles that see them
+//   attn_bwd_dkdv_bf16_d64 key-major: a wavefront owns 48 keys and walks over the query tiles that see them
 // Both matrix kernels recompute the weights from the stored log-sum-exp, so no online softmax is
 // needed, and both keep the operand whose rows they own in registers for the whole kernel.  Tiles
 // of the other operand go global -> LDS directly into the same XOR-swizzled ring as in the forward
@@ -17,7 +17,7 @@
 // LDS read), so neither P nor dS ever touches LDS.
 //
 // Register budget: both kernels run two wavefronts per SIMD - the dq kernel by forming the scores of
-// 32 keys at a time, the dk/dv kernel by owning 32 keys per wavefront.  S and dP are formed in both
+// 32 keys and 16 queries at a time, the dk/dv kernel by owning 48 keys per wavefront.  S and dP are formed in both
 // kernels (seven products for the five of the mathematics): the price of having no atomics on dq.
 #pragma once
 #include "kernels_mfma.hpp"
@@ -75,52 +75,6 @@ __device__ __forceinline__ void dma_tile_pair(const __bf16* a, const __bf16* b, 
         asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(a + off), "s"(lds_a + pass * 4096) : "memory", "m0");
         asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(b + off), "s"(lds_b + pass * 4096) : "memory", "m0");
     }
-}
-
-// Per-lane LDS offsets (elements) of the two fragment kinds under the swizzle: plain 16-byte row
-// fragments (row = lane % 32 of a 32-row block, feature step ks) and transposing reads (A operand
-// of a product whose contraction index runs over the tile's rows).
-struct FragOffsets {
-    int row_frag[4];     // [ks]
-    int tr_frag[2][2];   // [dt][second half of the 16-row step]
-};
-__device__ __forceinline__ FragOffsets frag_offsets(int lane) {
-    FragOffsets f;
-    const int n = lane & 31, h = lane >> 5;
-    const int fk = chunk_swizzle(n);
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks) f.row_frag[ks] = n * kD + 8 * ((2 * ks + h) ^ fk);
-    const int s16 = lane & 15, dblk = (lane >> 4) & 1;
-    const int v_row = 4 * h + (s16 >> 2);
-    const int v_chunk = 2 * dblk + ((s16 & 3) >> 1);
-    const int fv = chunk_swizzle(v_row);
-#pragma unroll
-    for (int dt = 0; dt < 2; ++dt)
-#pragma unroll
-        for (int sec = 0; sec < 2; ++sec)
-            f.tr_frag[dt][sec] = (v_row + 8 * sec) * kD + 8 * ((4 * dt + v_chunk) ^ (fv ^ (2 * sec))) + 4 * (s16 & 1);
-    return f;
-}
-__device__ __forceinline__ bf16x8 read_tr_frag(const __bf16* tile, const FragOffsets& f, int blk32, int g, int dt) {
-    const __bf16* vp = tile + (32 * blk32 + 16 * g) * kD;
-    const s16x4 lo = lds_read_tr(vp + f.tr_frag[dt][0]);
-    const s16x4 hi = lds_read_tr(vp + f.tr_frag[dt][1]);
-    typedef __attribute__((ext_vector_type(8))) short s16x8;
-    const s16x8 av = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-    return __builtin_bit_cast(bf16x8, av);
-}
-// Pack eight consecutive accumulator values of one 32x32 block into the B-operand fragment of the
-// following product.
-__device__ __forceinline__ bf16x8 pack8(const f32x16& a, int g) {
-    bf16x8 r;
-#pragma unroll
-    for (int jj = 0; jj < 4; ++jj) {
-        const f32x2 pp = {a[8 * g + 2 * jj], a[8 * g + 2 * jj + 1]};
-        const bf16x2 pb = __builtin_convertvector(pp, bf16x2);
-        r[2 * jj] = pb[0];
-        r[2 * jj + 1] = pb[1];
-    }
-    return r;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -319,7 +273,7 @@ attn_bwd_dq_bf16_d64(BwdParams p) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// dk, dv: a workgroup owns 128 keys (4 wavefronts x 32, two wavefronts per SIMD) and walks over the 64-row query
+// dk, dv: a workgroup owns 192 keys (4 wavefronts x 48, two wavefronts per SIMD) and walks over the 64-row query
 // tiles that can see them (all rows from the first frame that sees the block's first key).
 //   S = Q.K^T, dP = dO.V^T (A = Q / dO rows from LDS, B = K^T / V^T in registers)
 //   dV^T += dO^T.P, dK^T += Q^T.dS (A by transposing reads of the dO / Q tile, B = P / dS accumulators)
@@ -331,8 +285,8 @@ attn_bwd_dq_bf16_d64(BwdParams p) {
 // in the loop.
 //
 // The 16x16x32 shape of the matrix instruction, in the register layout of the forward kernel (kernels_mfma16.hpp).
-// Lane = (j, g), j = lane % 16, g = lane / 16.  A wavefront's 32 keys are two column blocks ck of 16; a 32-row unit of a
-// query tile is two row blocks rb of 16.  Operand row i of a row block is tile row 4 sg(i / 4) + i % 4, sg = (0, 2, 3, 1)
+// Lane = (j, g), j = lane % 16, g = lane / 16.  A wavefront's 48 keys are three column blocks ck of 16; a 32-row unit of
+// a query tile is two row blocks rb of 16.  Operand row i of a row block is tile row 4 sg(i / 4) + i % 4, sg = (0, 2, 3, 1)
 // (the order that keeps both kinds of fragment reads free of bank conflicts under the tile swizzle), so
 //   S[rb][ck], dP[rb][ck]   A = Q / dO rows (16-byte LDS reads), B = K^T / V^T (registers)
 //                           D: key 16 ck + j, rows 4 sg(g) + e of the block, e = 0..3
@@ -340,15 +294,22 @@ attn_bwd_dq_bf16_d64(BwdParams p) {
 //                           rows 4 sg(g) .. + 3 of the unit's first block, then of its second), B = P / dS: exactly the
 //                           eight values lane (j, g) holds of the unit's two blocks, packed
 //                           D: key 16 ck + j, features 16 fb + 4 g + e
-// A query tile is two units of 32 rows; per unit 16 MFMA for S and dP, 16 x (fma, exp2, mul) + 16 packed conversions,
-// 16 MFMA for dV and dK, 20 KB of LDS fragment reads.  (The same kernel on the 32x32x16 instruction - 16 of a block's
-// 32 rows per lane, 24 KB of reads per unit - measured 0.835 against 0.804 ms for the whole backward at 16 frames of
-// 336 tokens.  Also measured there and not kept: interleaving the matrix instructions of one unit with the vector
+// A query tile is two units of 32 rows; per unit 24 MFMA for S and dP, 24 x (fma, exp2, mul) + 24 packed conversions,
+// 24 MFMA for dV and dK, 20 KB of LDS fragment reads.  (The same kernel on the 32x32x16 instruction with 32 keys per
+// wavefront - 16 of a block's 32 rows per lane, 24 KB of reads per unit of 32 MFMA - measured 0.835 against 0.804 ms for
+// the whole backward at 16 frames of 336 tokens with 32 keys per wavefront on this instruction.  Also measured there and not kept: interleaving the matrix instructions of one unit with the vector
 // instructions of the other inside the wavefront, no gain - the second wavefront of the SIMD already fills those
 // slots; 64 keys per wavefront with one wavefront per SIMD, slower.)
 // ring depth: tiles t+1, t+2 in flight or landed while tile t is worked on, t+3 requested (three slots: 1 % slower;
 // three slots and three wavefronts per SIMD, which the registers allow with ten spills: 3 % slower)
 constexpr int kBwdKvSlots = 4;
+// 16-key column blocks per wavefront.  Every fragment of Q, dO and their transposes that comes out of LDS feeds one
+// matrix instruction per column block, so the LDS bytes per FLOP fall with the block count; the accumulators of dK^T
+// and dV^T and the K^T, V^T operands grow with it.  Three blocks (48 keys per wavefront, 192 per workgroup) are what
+// two wavefronts per SIMD leave room for: 252 VGPRs, no spills (two blocks: 178; four: 118 spilled dwords).  Measured
+// on one box, whole backward at 16 frames of 336 tokens: 0.776 ms with two blocks, 0.742 with three.
+constexpr int kBwdColBlocks = 3;
+constexpr int kBwdKeysPerWorkgroup = 4 * 16 * kBwdColBlocks;
 struct __attribute__((aligned(16))) SmemBwdKv {
     __bf16 q[kBwdKvSlots][kTileElems];
     __bf16 g[kBwdKvSlots][kTileElems];
@@ -357,6 +318,7 @@ struct __attribute__((aligned(16))) SmemBwdKv {
 
 __global__ void __launch_bounds__(256, 2)
 attn_bwd_dkdv_bf16_d64(BwdParams p) {
+    constexpr int NCK = kBwdColBlocks, kWaveKeys = 16 * NCK;
     __shared__ SmemBwdKv sm;
     const BwdItem wi = decode_bwd(p.BH, p.n_k_blocks);
     if (!wi.valid) return;
@@ -366,8 +328,8 @@ attn_bwd_dkdv_bf16_d64(BwdParams p) {
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int j = lane & 15, g = lane >> 4;
     auto sg = [](int x) { return (0x78 >> (2 * x)) & 3; };  // 0, 2, 3, 1
-    const int k0 = k_block * 128;
-    const int kw0 = k0 + wave * 32;
+    const int k0 = k_block * 4 * kWaveKeys;
+    const int kw0 = k0 + wave * kWaveKeys;
 
     const __bf16* qg = (const __bf16*)p.q + (int64_t)wi.bh * p.Sq * kD;
     const __bf16* gg = (const __bf16*)p.dout + (int64_t)wi.bh * p.Sq * kD;
@@ -377,10 +339,10 @@ attn_bwd_dkdv_bf16_d64(BwdParams p) {
     const float* dl_g = p.neg_delta + (int64_t)wi.bh * p.Sq;
 
     // ---- this wavefront's keys: B operands K^T, V^T and the visibility bound of the lane's two keys ----
-    int key[2], rmin_lane[2];
-    bf16x8 kf[2][2], vf[2][2];  // [ck][ks]
+    int key[NCK], rmin_lane[NCK];
+    bf16x8 kf[NCK][2], vf[NCK][2];  // [ck][ks]
 #pragma unroll
-    for (int ck = 0; ck < 2; ++ck) {
+    for (int ck = 0; ck < NCK; ++ck) {
         key[ck] = kw0 + 16 * ck + j;
         const int kc = min(key[ck], p.Sk - 1);  // ragged tail: a duplicate column, never stored
         rmin_lane[ck] = (kc / p.T - p.P) * p.T;  // <= 0: visible to every row
@@ -391,18 +353,18 @@ attn_bwd_dkdv_bf16_d64(BwdParams p) {
         }
     }
     const bool wave_active = kw0 < p.Sk;
-    const int kw_first = min(kw0, p.Sk - 1), kw_last = min(kw0 + 31, p.Sk - 1);
+    const int kw_first = min(kw0, p.Sk - 1), kw_last = min(kw0 + kWaveKeys - 1, p.Sk - 1);
     const int rmin_wave = (kw_first / p.T - p.P) * p.T;  // tiles ending at or below it are skipped by this wavefront
     const int rmax_wave = (kw_last / p.T - p.P) * p.T;   // tiles starting at or above it need no mask
     const int rmin_wg = max(0, (k0 / p.T - p.P) * p.T);
     const int t_begin = rmin_wg / 64;
     const int t_end = (p.Sq + 63) / 64;
 
-    f32x4 dk_acc[4][2], dv_acc[4][2];  // [fb][ck]
+    f32x4 dk_acc[4][NCK], dv_acc[4][NCK];  // [fb][ck]
 #pragma unroll
     for (int a = 0; a < 4; ++a)
 #pragma unroll
-        for (int b = 0; b < 2; ++b)
+        for (int b = 0; b < NCK; ++b)
 #pragma unroll
             for (int e = 0; e < 4; ++e) { dk_acc[a][b][e] = 0.f; dv_acc[a][b][e] = 0.f; }
     const float c = p.scale_log2e;
@@ -470,7 +432,7 @@ attn_bwd_dkdv_bf16_d64(BwdParams p) {
             const bool ragged = i0 + 64 > p.Sq;
 #pragma unroll
             for (int qb = 0; qb < 2; ++qb) {
-                f32x4 s_acc[2][2], dp_acc[2][2];  // [rb][ck]
+                f32x4 s_acc[2][NCK], dp_acc[2][NCK];  // [rb][ck]
                 f32x4 lse4[2];                    // [rb]
                 bf16x8 qa[2][2], ga[2][2];        // [rb][ks]
 #pragma unroll
@@ -483,7 +445,7 @@ attn_bwd_dkdv_bf16_d64(BwdParams p) {
                     lse4[rb] = *(const f32x4*)(&sm.ld[slot][0][32 * qb + 16 * rb + vec_row]);
                     const f32x4 nd = *(const f32x4*)(&sm.ld[slot][1][32 * qb + 16 * rb + vec_row]);
 #pragma unroll
-                    for (int ck = 0; ck < 2; ++ck) {
+                    for (int ck = 0; ck < NCK; ++ck) {
                         dp_acc[rb][ck] = nd;  // dP starts at -delta
 #pragma unroll
                         for (int e = 0; e < 4; ++e) s_acc[rb][ck][e] = 0.f;
@@ -494,7 +456,7 @@ attn_bwd_dkdv_bf16_d64(BwdParams p) {
 #pragma unroll
                     for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
-                        for (int ck = 0; ck < 2; ++ck) {
+                        for (int ck = 0; ck < NCK; ++ck) {
                             s_acc[rb][ck] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qa[rb][ks], kf[ck][ks], s_acc[rb][ck], 0, 0, 0);
                             dp_acc[rb][ck] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ga[rb][ks], vf[ck][ks], dp_acc[rb][ck], 0, 0, 0);
                         }
@@ -506,23 +468,23 @@ attn_bwd_dkdv_bf16_d64(BwdParams p) {
                         for (int e = 0; e < 4; ++e) {
                             const int i = i0 + 32 * qb + 16 * rb + vec_row + e;
 #pragma unroll
-                            for (int ck = 0; ck < 2; ++ck)
+                            for (int ck = 0; ck < NCK; ++ck)
                                 if (i < rmin_lane[ck] || i >= p.Sq) s_acc[rb][ck][e] = -INFINITY;
                         }
                 }
 #pragma unroll
                 for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
-                    for (int ck = 0; ck < 2; ++ck)
+                    for (int ck = 0; ck < NCK; ++ck)
 #pragma unroll
                         for (int e = 0; e < 4; ++e) {
                             const float pr = __builtin_amdgcn_exp2f(__builtin_fmaf(s_acc[rb][ck][e], c, -lse4[rb][e]));
                             s_acc[rb][ck][e] = pr;                         // P
                             dp_acc[rb][ck][e] = pr * dp_acc[rb][ck][e];    // dS = P (dP - delta)
                         }
-                bf16x8 pk[2], dsk[2];  // [ck]
+                bf16x8 pk[NCK], dsk[NCK];  // [ck]
 #pragma unroll
-                for (int ck = 0; ck < 2; ++ck) {
+                for (int ck = 0; ck < NCK; ++ck) {
                     pk[ck] = pack2(s_acc[0][ck], s_acc[1][ck]);
                     dsk[ck] = pack2(dp_acc[0][ck], dp_acc[1][ck]);
                 }
@@ -531,7 +493,7 @@ attn_bwd_dkdv_bf16_d64(BwdParams p) {
                     const bf16x8 gt = read_t(gs_, qb, fb);  // dO^T
                     const bf16x8 qt = read_t(qs_, qb, fb);  // Q^T
 #pragma unroll
-                    for (int ck = 0; ck < 2; ++ck) {
+                    for (int ck = 0; ck < NCK; ++ck) {
                         dv_acc[fb][ck] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(gt, pk[ck], dv_acc[fb][ck], 0, 0, 0);
                         dk_acc[fb][ck] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qt, dsk[ck], dk_acc[fb][ck], 0, 0, 0);
                     }
@@ -544,7 +506,7 @@ attn_bwd_dkdv_bf16_d64(BwdParams p) {
 
     if (!wave_active) return;
 #pragma unroll
-    for (int ck = 0; ck < 2; ++ck) {
+    for (int ck = 0; ck < NCK; ++ck) {
         if (key[ck] >= p.Sk) continue;
         __bf16* dkg = (__bf16*)p.dk + ((int64_t)wi.bh * p.Scap + key[ck]) * kD;
         __bf16* dvg = (__bf16*)p.dv + ((int64_t)wi.bh * p.Scap + key[ck]) * kD;

@@ -528,7 +528,7 @@ int nfd_block_causal_attn_bwd(nfd_attn_t* h, const void* q, const void* k, const
     p.dq = dq; p.dk = dk; p.dv = dv;
     p.BH = (int)BH; p.Sq = (int)Sq; p.Sk = (int)Sk; p.Scap = F * T; p.T = T; p.P = kv_frames - q_frames;
     p.n_q_tiles = (int)((Sq + nfd::mfma::kBM - 1) / nfd::mfma::kBM);
-    p.n_k_blocks = (int)((Sk + 127) / 128);  // 4 wavefronts x 32 keys
+    p.n_k_blocks = (int)((Sk + nfd::mfma::kBwdKeysPerWorkgroup - 1) / nfd::mfma::kBwdKeysPerWorkgroup);
     p.scale = scale;
     p.scale_log2e = scale * nfd::kLog2e;
     if (BH * p.n_q_tiles > (int64_t)0x7fffffff || BH * p.n_k_blocks > (int64_t)0x7fffffff)
